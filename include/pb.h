@@ -1,0 +1,174 @@
+/*
+ * pb.h -- C ABI of the MI355X (gfx950) phrase-boosting tree for shallow-fusion context biasing.
+ *
+ * The library compiles a list of tokenized key phrases into a flattened Aho-Corasick-style
+ * boosting tree (goto arcs sorted by token id, failure links, per-state backoff scores,
+ * end-of-phrase flags) on the host, uploads it once, and evaluates it on the GPU for whole
+ * batches of hypotheses: dense per-vocabulary boost scores and next states, and the fused
+ * "acoustic log-prob + lambda * boost" selection step (greedy argmax or per-utterance beam top-k).
+ *
+ * Conventions for every entry point
+ *   - returns a pb_status code; never throws, never aborts; PB_OK == 0;
+ *   - "d_" pointers are DEVICE memory owned by the caller, on the device the tree was built for,
+ *     which must be the current HIP device of the calling thread; plain pointers are HOST memory;
+ *   - step calls (pb_score, pb_fuse_*) are asynchronous on `hip_stream` (a hipStream_t, NULL = the
+ *     default stream); they allocate nothing, synchronise nothing and read no host memory besides
+ *     their scalar arguments, so they may be captured into a HIP graph;
+ *   - state ids: 0 is the root (the initial state of every hypothesis); ids follow breadth-first
+ *     order with the children of a state visited by ascending token id, so the arc with index j
+ *     of the (from_state, token)-sorted arc table leads to state j + 1;
+ *   - a state id outside [0, num_states) in a step call does not fault: the row's outputs are
+ *     filled with -1 (ids) and NaN (scores);
+ *   - all scores are IEEE fp32; sums run in the order stated below with one rounding per
+ *     operation and no fused multiply-add.
+ */
+#ifndef PB_H_
+#define PB_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pb_tree pb_tree; /* opaque; owns its host and device arrays */
+
+enum pb_status {
+  PB_OK = 0,
+  PB_EINVAL = -1,       /* malformed argument (null pointer, empty phrase, blank inside a phrase, ...) */
+  PB_ERANGE = -2,       /* a token or size outside its range                                            */
+  PB_ENOMEM = -3,       /* host or device allocation failed                                             */
+  PB_EHIP = -4,         /* a HIP runtime call failed (no device, launch error)                          */
+  PB_EUNSUPPORTED = -5  /* valid request outside the limits of this build (see each call)               */
+};
+
+enum pb_weight_mode {
+  PB_W_UNIFORM = 0, /* every arc created by phrase i scores weights[i]                                  */
+  PB_W_LOGDEPTH = 1 /* depth 1: weights[i] (= c0); depth d > 1: weights[i] * beta + ln(d)
+                       (Sec. II-B, score distribution; Alg. 1 Stage 1, arc.score)                       */
+};
+
+typedef struct {
+  int32_t vocab_size;         /* V > 0                                                                  */
+  int32_t blank_id;           /* in [0, V), or -1 for a blank-free vocabulary                           */
+  int32_t weight_mode;        /* enum pb_weight_mode                                                    */
+  float beta;                 /* depth scaling of PB_W_LOGDEPTH (paper's example: 2)                    */
+  float unk_score;            /* c_unk: score of the root self-loop taken by tokens that start no phrase
+                                 (Sec. II-B; Alg. 1 Stage 2); default 0                                 */
+  int32_t final_zero_backoff; /* 1: end-of-phrase states back off with score 0 (Sec. II-B, the paper's
+                                 rule); 0: every state backs off with acc(fail) - acc(state)            */
+  int32_t device;             /* HIP device ordinal to upload to; -1 = host-only tree (no GPU needed,
+                                 step calls on it return PB_EINVAL)                                     */
+} pb_build_opts;
+
+typedef struct {
+  int32_t num_states;     /* N, root included                        */
+  int32_t num_arcs;       /* N - 1                                   */
+  int32_t max_depth;      /* longest phrase                          */
+  int32_t max_fail_chain; /* most failure hops from any state to root */
+  int32_t root_degree;    /* tokens that start a phrase              */
+  int32_t vocab_size;
+  int32_t blank_id;
+  int64_t device_bytes;   /* size of the uploaded tree, 0 if host-only */
+} pb_tree_info;
+
+/* Host view of the flat arrays the kernels read (owned by the tree; valid until pb_free). */
+typedef struct {
+  const int32_t* arc_begin; /* [N]   first arc of a state in the sorted arc table                       */
+  const int32_t* arc_count; /* [N]   number of arcs leaving the state                                   */
+  const int32_t* fail;      /* [N]   failure link (longest proper suffix that is a tree prefix)         */
+  const float* backoff;     /* [N]   backoff score of the state, fp32                                   */
+  const uint8_t* is_final;  /* [N]   1 if a phrase ends at the state                                    */
+  const int32_t* depth;     /* [N]                                                                      */
+  const int32_t* parent;    /* [N]   -1 for the root                                                    */
+  const int32_t* arc_token; /* [N-1] token of arc j (rows sorted strictly ascending); target = j + 1    */
+  const float* arc_score;   /* [N-1] score of arc j, fp32                                               */
+  const double* acc;        /* [N]   accumulated score root -> state, double                            */
+  const float* root_score;  /* [V]   dense root row: arc score or c_unk                                 */
+  const int32_t* root_next; /* [V]   dense root row: depth-1 state or 0 (self-loop)                     */
+} pb_host_view;
+
+/*
+ * pb_build -- compile the context list into the tree (Alg. 1, Stages 1 and 2; Sec. II-B).
+ *   tokens[offsets[i] .. offsets[i+1]) are the token ids of phrase i; weights[i] is its context
+ *   score c0 (NULL: all 1.0).  An arc takes the score of the phrase that creates it; later
+ *   phrases sharing the prefix reuse it.  Duplicate phrases, phrases that are prefixes of others
+ *   and one-token phrases are legal; n_phrases == 0 gives a root-only tree.
+ *   Host-synchronous.  On success *out receives the tree (free with pb_free); on failure *out is
+ *   untouched.  PB_EINVAL: null argument, V <= 0, blank_id outside [-1, V), unknown weight_mode,
+ *   offsets not strictly increasing (an empty phrase), a phrase containing blank_id.
+ *   PB_ERANGE: a token outside [0, V).  PB_EHIP / PB_ENOMEM: upload failed.
+ */
+int pb_build(const int32_t* tokens, const int64_t* offsets, int64_t n_phrases, const float* weights,
+             const pb_build_opts* opts, pb_tree** out);
+
+/* Releases host and device memory of the tree; NULL is a no-op. */
+int pb_free(pb_tree* tree);
+
+int pb_info(const pb_tree* tree, pb_tree_info* out);
+
+/* Host view of the compiled arrays, for inspection and structural tests. */
+int pb_host_arrays(const pb_tree* tree, pb_host_view* out);
+
+/* Token string spelled by the path root -> state (host-side).  Writes min(len, cap) tokens to
+   out_tokens and the full length to *out_len.  PB_ERANGE for an unknown state. */
+int pb_state_prefix(const pb_tree* tree, int32_t state, int32_t* out_tokens, int32_t cap, int32_t* out_len);
+
+/*
+ * pb_score -- whole-vocabulary query, the tree's get_scores (Alg. 1 Stage 3; Sec. II-B).
+ *   For every hypothesis b and every token v: starting at s = d_states[b] with p = 0, while s is
+ *   not the root and has no arc on v, p += backoff(s) and s = fail(s); then
+ *     d_scores[b,v] = p + arc_score(s,v), d_next[b,v] = target(s,v)      if s has an arc on v,
+ *     d_scores[b,v] = p + c_unk,          d_next[b,v] = 0                 otherwise (root self-loop).
+ *   The blank column is 0 with next = d_states[b].
+ *   d_states int32[B]; d_scores float[B,V] row-major; d_next int32[B,V] or NULL to skip it.
+ *   B == 0 is a no-op.
+ */
+int pb_score(const pb_tree* tree, const int32_t* d_states, int32_t B, float* d_scores, int32_t* d_next,
+             void* hip_stream);
+
+/*
+ * pb_fuse_step -- one greedy shallow-fusion step (Eq. 1; Alg. 1 Stage 3) without materialising
+ * the [B,V] boost.  For every hypothesis b:
+ *     fused[v]        = d_logp[b*row_stride + v] + (alpha * score(d_states_in[b], v))
+ *     d_tokens[b]     = argmax_v fused[v], the lowest token id among equal maxima
+ *     d_states_out[b] = next(d_states_in[b], d_tokens[b])   (unchanged when the token is the blank)
+ *     d_scores[b]     = fused[d_tokens[b]]
+ *   row_stride >= V in elements.  d_states_out may alias d_states_in.  NaN log-probs are a
+ *   precondition violation (the result is then unspecified but in range); -inf is legal.
+ */
+int pb_fuse_step(const pb_tree* tree, const float* d_logp, int64_t row_stride, const int32_t* d_states_in,
+                 float alpha, int32_t B, int32_t* d_tokens, int32_t* d_states_out, float* d_scores,
+                 void* hip_stream);
+
+/*
+ * pb_fuse_frames -- T greedy steps in one launch for the case where all frames exist up front
+ * (CTC-style decoding, Sec. II-C): frame t uses d_logp[t*frame_stride + b*row_stride + v] and the
+ * states produced by frame t-1 (d_states0 for t = 0).  Outputs are [T,B] row-major: the token,
+ * the state after the frame and the fused score of every frame; identical to T calls of
+ * pb_fuse_step.  T == 0 or B == 0 is a no-op.
+ */
+int pb_fuse_frames(const pb_tree* tree, const float* d_logp, int64_t frame_stride, int64_t row_stride,
+                   const int32_t* d_states0, float alpha, int32_t T, int32_t B, int32_t* d_tokens,
+                   int32_t* d_states, float* d_scores, void* hip_stream);
+
+/*
+ * pb_fuse_step_beam -- one beam-search step: expansion scores, pruning and the state gather by
+ * parent (Alg. 1 Stage 3: hyps_expansion_score, prune_expanded, S[t]).  Hypotheses u*K .. u*K+K-1
+ * are the beams of utterance u.  For every candidate (k, v) of utterance u
+ *     total = d_hyp_scores[u*K+k] + (d_logp[(u*K+k)*row_stride + v] + (alpha * score(state[u*K+k], v)))
+ *   the K candidates that come first by (total descending, k*V+v ascending) are written, in that
+ *   order, to slots u*K .. u*K+K-1: d_tokens = v, d_parents = k, d_states_out = next(state of the
+ *   parent, v), d_scores_out = total.  -inf hypothesis scores (dead beams) are legal.
+ *   1 <= K <= 32.  d_states_out must not alias d_states_in.  U == 0 is a no-op.
+ */
+int pb_fuse_step_beam(const pb_tree* tree, const float* d_logp, int64_t row_stride, const float* d_hyp_scores,
+                      const int32_t* d_states_in, float alpha, int32_t U, int32_t K, int32_t* d_tokens,
+                      int32_t* d_parents, int32_t* d_states_out, float* d_scores_out, void* hip_stream);
+
+const char* pb_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PB_H_ */

@@ -1,0 +1,49 @@
+"""Builds libpb.so (HIP kernels + host tree compiler + C ABI) in-tree for gfx950."""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(PKG)
+CSRC = os.path.join(PKG, "csrc")
+LIB = os.path.join(PKG, "libpb.so")
+SOURCES = ["pb_compile.cpp", "pb_kernels.hip", "pb_api.hip"]
+HEADERS = ["pb_tree.hpp", "pb_kernels.hpp", os.path.join(ROOT, "include", "pb.h")]
+
+
+def hipcc_command(out: str = LIB) -> list:
+    return [
+        "hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+        "-ffp-contract=off",
+        # packed-fp32 instructions stay off: some of their forms have given wrong results on the test machines
+        "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+        "-Wall", "-Wextra", "-Wno-unused-parameter",
+        "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+        "-o", out,
+    ] + [os.path.join(CSRC, s) for s in SOURCES]
+
+
+def stale() -> bool:
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    deps = [os.path.join(CSRC, s) for s in SOURCES] + [h if os.path.isabs(h) else os.path.join(CSRC, h) for h in HEADERS]
+    return any(os.path.getmtime(d) > t for d in deps)
+
+
+def build(force: bool = True, verbose: bool = False) -> str:
+    """Compiles the library; with force=False only when it is missing."""
+    if not force and os.path.exists(LIB):
+        return LIB
+    cmd = hipcc_command()
+    if verbose:
+        print(" ".join(cmd), file=sys.stderr)
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    build(force=True, verbose=True)
+    print(LIB)

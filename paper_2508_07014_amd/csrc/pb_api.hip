@@ -1,0 +1,205 @@
+// C ABI of the phrase-boosting tree library (declared in include/pb.h): argument checks, upload of
+// the compiled tree, and dispatch to the kernel launchers.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <new>
+
+#include "pb.h"
+#include "pb_kernels.hpp"
+#include "pb_tree.hpp"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+
+size_t padded(size_t bytes) { return (bytes + kAlign - 1) / kAlign * kAlign; }
+
+// Uploads the flat arrays as one device allocation.  The device stays current only inside the call.
+int upload(pb_tree* tr, int device) {
+  const pb::HostTree& h = tr->host;
+  const size_t n_state = h.state.size() * sizeof(pb::StateRec);
+  const size_t n_arc = h.arc.size() * sizeof(pb::ArcRec);
+  const size_t n_rs = h.root_score.size() * sizeof(float);
+  const size_t n_rn = h.root_next.size() * sizeof(int32_t);
+  const size_t total = padded(n_state) + padded(n_arc) + padded(n_rs) + padded(n_rn);
+  int prev = 0;
+  if (hipGetDevice(&prev) != hipSuccess) { (void)hipGetLastError(); return PB_EHIP; }
+  if (hipSetDevice(device) != hipSuccess) { (void)hipGetLastError(); return PB_EHIP; }
+  int rc = PB_OK;
+  char* slab = nullptr;
+  if (hipMalloc(reinterpret_cast<void**>(&slab), total) != hipSuccess) {
+    (void)hipGetLastError();
+    rc = PB_ENOMEM;
+  } else {
+    char* p = slab;
+    auto put = [&](const void* src, size_t bytes) -> const void* {
+      char* dst = p;
+      if (bytes && rc == PB_OK && hipMemcpy(dst, src, bytes, hipMemcpyHostToDevice) != hipSuccess) rc = PB_EHIP;
+      p += padded(bytes);
+      return dst;
+    };
+    tr->dev.state = static_cast<const pb::StateRec*>(put(h.state.data(), n_state));
+    tr->dev.arc = static_cast<const pb::ArcRec*>(put(h.arc.data(), n_arc));
+    tr->dev.root_score = static_cast<const float*>(put(h.root_score.data(), n_rs));
+    tr->dev.root_next = static_cast<const int32_t*>(put(h.root_next.data(), n_rn));
+    tr->dev.num_states = static_cast<int32_t>(h.state.size());
+    tr->dev.vocab_size = h.vocab_size;
+    tr->dev.blank_id = h.blank_id;
+    if (rc != PB_OK) {
+      (void)hipGetLastError();
+      (void)hipFree(slab);
+      slab = nullptr;
+    }
+  }
+  (void)hipSetDevice(prev);
+  if (rc == PB_OK) {
+    tr->slab = slab;
+    tr->device_bytes = static_cast<int64_t>(total);
+    tr->device = device;
+  }
+  return rc;
+}
+
+bool on_device(const pb_tree* t) { return t && t->slab != nullptr; }
+
+}  // namespace
+
+extern "C" {
+
+int pb_build(const int32_t* tokens, const int64_t* offsets, int64_t n_phrases, const float* weights,
+             const pb_build_opts* opts, pb_tree** out) {
+  if (!opts || !out) return PB_EINVAL;
+  if (opts->device < -1) return PB_EINVAL;
+  pb_tree* tr = new (std::nothrow) pb_tree();
+  if (!tr) return PB_ENOMEM;
+  int rc = pb::compile_tree(tokens, offsets, n_phrases, weights, *opts, tr->host);
+  if (rc == PB_OK && opts->device >= 0) rc = upload(tr, opts->device);
+  if (rc != PB_OK) {
+    delete tr;
+    return rc;
+  }
+  *out = tr;
+  return PB_OK;
+}
+
+int pb_free(pb_tree* tree) {
+  if (!tree) return PB_OK;
+  int rc = PB_OK;
+  if (tree->slab) {
+    int prev = 0;
+    (void)hipGetDevice(&prev);
+    (void)hipSetDevice(tree->device);
+    if (hipFree(tree->slab) != hipSuccess) { (void)hipGetLastError(); rc = PB_EHIP; }
+    (void)hipSetDevice(prev);
+  }
+  delete tree;
+  return rc;
+}
+
+int pb_info(const pb_tree* tree, pb_tree_info* out) {
+  if (!tree || !out) return PB_EINVAL;
+  const pb::HostTree& h = tree->host;
+  out->num_states = static_cast<int32_t>(h.state.size());
+  out->num_arcs = static_cast<int32_t>(h.arc.size());
+  out->max_depth = h.max_depth;
+  out->max_fail_chain = h.max_fail_chain;
+  out->root_degree = h.root_degree;
+  out->vocab_size = h.vocab_size;
+  out->blank_id = h.blank_id;
+  out->device_bytes = tree->device_bytes;
+  return PB_OK;
+}
+
+int pb_host_arrays(const pb_tree* tree, pb_host_view* out) {
+  if (!tree || !out) return PB_EINVAL;
+  const pb::HostTree& h = tree->host;
+  out->arc_begin = h.arc_begin.data();
+  out->arc_count = h.arc_count.data();
+  out->fail = h.fail.data();
+  out->backoff = h.backoff.data();
+  out->is_final = h.is_final.data();
+  out->depth = h.depth.data();
+  out->parent = h.parent.data();
+  out->arc_token = h.arc_token.data();
+  out->arc_score = h.arc_score.data();
+  out->acc = h.acc.data();
+  out->root_score = h.root_score.data();
+  out->root_next = h.root_next.data();
+  return PB_OK;
+}
+
+int pb_state_prefix(const pb_tree* tree, int32_t state, int32_t* out_tokens, int32_t cap, int32_t* out_len) {
+  if (!tree || !out_len || cap < 0 || (cap > 0 && !out_tokens)) return PB_EINVAL;
+  const pb::HostTree& h = tree->host;
+  if (state < 0 || state >= static_cast<int32_t>(h.state.size())) return PB_ERANGE;
+  const int32_t len = h.depth[state];
+  *out_len = len;
+  int32_t s = state;
+  for (int32_t d = len - 1; d >= 0; --d) {  // the arc into state s has index s - 1
+    if (d < cap) out_tokens[d] = h.arc_token[s - 1];
+    s = h.parent[s];
+  }
+  return PB_OK;
+}
+
+int pb_score(const pb_tree* tree, const int32_t* d_states, int32_t B, float* d_scores, int32_t* d_next,
+             void* hip_stream) {
+  if (!on_device(tree) || B < 0) return PB_EINVAL;
+  if (B == 0) return PB_OK;
+  if (!d_states || !d_scores) return PB_EINVAL;
+  return pb::launch_score(tree->dev, d_states, B, d_scores, d_next, static_cast<hipStream_t>(hip_stream));
+}
+
+int pb_fuse_step(const pb_tree* tree, const float* d_logp, int64_t row_stride, const int32_t* d_states_in,
+                 float alpha, int32_t B, int32_t* d_tokens, int32_t* d_states_out, float* d_scores,
+                 void* hip_stream) {
+  if (!on_device(tree) || B < 0) return PB_EINVAL;
+  if (B == 0) return PB_OK;
+  if (!d_logp || !d_states_in || !d_tokens || !d_states_out || !d_scores) return PB_EINVAL;
+  if (row_stride < tree->dev.vocab_size) return PB_EINVAL;
+  return pb::launch_fuse(tree->dev, d_logp, 0, row_stride, d_states_in, alpha, 1, B, d_tokens, d_states_out,
+                         d_scores, static_cast<hipStream_t>(hip_stream));
+}
+
+int pb_fuse_frames(const pb_tree* tree, const float* d_logp, int64_t frame_stride, int64_t row_stride,
+                   const int32_t* d_states0, float alpha, int32_t T, int32_t B, int32_t* d_tokens,
+                   int32_t* d_states, float* d_scores, void* hip_stream) {
+  if (!on_device(tree) || B < 0 || T < 0) return PB_EINVAL;
+  if (B == 0 || T == 0) return PB_OK;
+  if (!d_logp || !d_states0 || !d_tokens || !d_states || !d_scores) return PB_EINVAL;
+  if (row_stride < tree->dev.vocab_size || frame_stride < 0) return PB_EINVAL;
+  return pb::launch_fuse(tree->dev, d_logp, frame_stride, row_stride, d_states0, alpha, T, B, d_tokens, d_states,
+                         d_scores, static_cast<hipStream_t>(hip_stream));
+}
+
+int pb_fuse_step_beam(const pb_tree* tree, const float* d_logp, int64_t row_stride, const float* d_hyp_scores,
+                      const int32_t* d_states_in, float alpha, int32_t U, int32_t K, int32_t* d_tokens,
+                      int32_t* d_parents, int32_t* d_states_out, float* d_scores_out, void* hip_stream) {
+  if (!on_device(tree) || U < 0) return PB_EINVAL;
+  if (K < 1) return PB_EINVAL;
+  if (K > 32) return PB_EUNSUPPORTED;
+  if (U == 0) return PB_OK;
+  if (!d_logp || !d_hyp_scores || !d_states_in || !d_tokens || !d_parents || !d_states_out || !d_scores_out)
+    return PB_EINVAL;
+  if (row_stride < tree->dev.vocab_size) return PB_EINVAL;
+  if (d_states_out == d_states_in) return PB_EINVAL;
+  if (static_cast<int64_t>(K) * tree->dev.vocab_size >= INT32_MAX) return PB_EUNSUPPORTED;
+  if (static_cast<int64_t>(U) * K > INT32_MAX) return PB_EUNSUPPORTED;
+  return pb::launch_beam(tree->dev, d_logp, row_stride, d_hyp_scores, d_states_in, alpha, U, K, d_tokens, d_parents,
+                         d_states_out, d_scores_out, static_cast<hipStream_t>(hip_stream));
+}
+
+const char* pb_strerror(int code) {
+  switch (code) {
+    case PB_OK: return "ok";
+    case PB_EINVAL: return "invalid argument";
+    case PB_ERANGE: return "value out of range";
+    case PB_ENOMEM: return "out of memory";
+    case PB_EHIP: return "HIP runtime error";
+    case PB_EUNSUPPORTED: return "unsupported size";
+    default: return "unknown error";
+  }
+}
+
+}  // extern "C"

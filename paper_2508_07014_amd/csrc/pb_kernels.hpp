@@ -1,0 +1,24 @@
+// Launch wrappers of the HIP kernels (defined in pb_kernels.hip).  Each returns a pb_status.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "pb_tree.hpp"
+
+namespace pb {
+
+constexpr int kMaxChunk = 8192;   // tokens per LDS pass of the fused kernels (64 KiB of 8-byte entries)
+constexpr int kScoreTile = 2048;  // tokens per workgroup of the score kernel (16 KiB of LDS)
+
+int launch_score(const DeviceTree& t, const int32_t* d_states, int32_t B, float* d_scores, int32_t* d_next,
+                 hipStream_t stream);
+
+// T == 1 with frame_stride == 0 is the single step.
+int launch_fuse(const DeviceTree& t, const float* d_logp, int64_t frame_stride, int64_t row_stride,
+                const int32_t* d_states0, float alpha, int32_t T, int32_t B, int32_t* d_tokens, int32_t* d_states,
+                float* d_scores, hipStream_t stream);
+
+int launch_beam(const DeviceTree& t, const float* d_logp, int64_t row_stride, const float* d_hyp,
+                const int32_t* d_states_in, float alpha, int32_t U, int32_t K, int32_t* d_tokens, int32_t* d_parents,
+                int32_t* d_states_out, float* d_scores_out, hipStream_t stream);
+
+}  // namespace pb

@@ -1,0 +1,58 @@
+// Internal layout of a compiled boosting tree: host arrays plus their device mirror.
+#pragma once
+#include <cstdint>
+#include <vector>
+
+#include "pb.h"
+
+namespace pb {
+
+// One 16-byte record per state: everything a failure-chain hop needs in a single load.
+struct alignas(16) StateRec {
+  int32_t arc_begin;  // first arc of the state in the (from_state, token)-sorted arc table
+  int32_t arc_count;  // arcs leaving the state
+  int32_t fail;       // failure link
+  float backoff;      // backoff score paid when the state is abandoned
+};
+
+// One 8-byte record per arc; the arc with index j leads to state j + 1.
+struct alignas(8) ArcRec {
+  int32_t token;
+  float score;
+};
+
+// Device mirror (one allocation, sub-arrays aligned to 256 bytes).
+struct DeviceTree {
+  const StateRec* state = nullptr;  // [N]
+  const ArcRec* arc = nullptr;      // [N-1]
+  const float* root_score = nullptr;  // [V]
+  const int32_t* root_next = nullptr;  // [V]
+  int32_t num_states = 0;
+  int32_t vocab_size = 0;
+  int32_t blank_id = -1;
+};
+
+struct HostTree {
+  int32_t vocab_size = 0, blank_id = -1;
+  int32_t max_depth = 0, max_fail_chain = 0, root_degree = 0;
+  std::vector<StateRec> state;
+  std::vector<ArcRec> arc;
+  std::vector<int32_t> arc_begin, arc_count, fail, depth, parent, arc_token, root_next;
+  std::vector<float> backoff, arc_score, root_score;
+  std::vector<uint8_t> is_final;
+  std::vector<double> acc;
+};
+
+// Alg. 1 Stages 1-2 on the host.  Returns a pb_status.
+int compile_tree(const int32_t* tokens, const int64_t* offsets, int64_t n_phrases, const float* weights,
+                 const pb_build_opts& opts, HostTree& out);
+
+}  // namespace pb
+
+struct pb_tree {
+  pb::HostTree host;
+  pb::DeviceTree dev;
+  void* slab = nullptr;  // device allocation backing `dev`
+  int64_t device_bytes = 0;
+  int device = -1;
+};

@@ -1,0 +1,186 @@
+"""Host tree compiler (pb_build with device = -1) and C-ABI surface, without a GPU.
+
+The compiled flat arrays are compared state by state with the oracle's tree (canonical numbering
+makes ids comparable), and a plain numpy reading of the flat arrays reproduces the oracle's rows.
+"""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2508_07014_amd as pb
+import pb_workloads as W
+from oracle import OracleTree
+from oracle.pb_oracle import W_LOGDEPTH, W_UNIFORM
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _both(tokens, offsets, V, blank, **kw):
+    ot = OracleTree(tokens, offsets, V, blank, weights=kw.get("weights"), weight_mode=kw.get("weight_mode", 0),
+                    beta=kw.get("beta", 2.0), unk_score=kw.get("unk_score", 0.0),
+                    final_zero_backoff=kw.get("final_zero_backoff", True))
+    tr = pb.pb_build(tokens, offsets, V, blank, device=-1, **kw)
+    return ot, tr
+
+
+def _compare_trees(ot, tr):
+    info = pb.pb_info(tr)
+    h = pb.pb_host_arrays(tr)
+    n = ot.num_states
+    assert info["num_states"] == n and info["num_arcs"] == n - 1 and info["max_depth"] == ot.max_depth
+    chain_max = 0
+    for s in range(n):
+        nd = ot.node(s)
+        assert h["depth"][s] == nd["depth"] and h["fail"][s] == nd["fail"] and h["parent"][s] == nd["parent"]
+        assert bool(h["is_final"][s]) == nd["final"]
+        assert h["acc"][s] == nd["acc"]
+        assert h["backoff"][s] == np.float32(nd["bw"])
+        if s:
+            assert h["arc_token"][s - 1] == nd["token"] and h["arc_score"][s - 1] == np.float32(nd["arcw"])
+        toks = h["arc_token"][h["arc_begin"][s]:h["arc_begin"][s] + h["arc_count"][s]]
+        assert np.all(np.diff(toks) > 0)                      # rows strictly sorted by token
+        for j, v in enumerate(toks):
+            assert ot.child(s, int(v)) == h["arc_begin"][s] + j + 1
+        hops, x = 0, s
+        while x:
+            x = h["fail"][x]
+            hops += 1
+        chain_max = max(chain_max, hops)
+    assert info["max_fail_chain"] == chain_max
+    assert info["root_degree"] == h["arc_count"][0]
+
+
+def _rows_from_flat(h, V, blank, unk, s):
+    """Dense (score, next) row of state s read off the flat arrays: deepest chain state wins."""
+    score = np.empty(V, np.float32)
+    nxt = np.empty(V, np.int32)
+    chain, p, x = [], np.float32(0), s
+    while x:
+        chain.append((x, p))
+        p = np.float32(p + h["backoff"][x])
+        x = h["fail"][x]
+    score[:] = p + h["root_score"]
+    nxt[:] = h["root_next"]
+    for x, px in reversed(chain):
+        b, c = h["arc_begin"][x], h["arc_count"][x]
+        tk = h["arc_token"][b:b + c]
+        score[tk] = px + h["arc_score"][b:b + c]
+        nxt[tk] = np.arange(b + 1, b + c + 1)
+    if blank >= 0:
+        score[blank] = 0
+        nxt[blank] = s
+    return score, nxt
+
+
+@pytest.mark.parametrize("seed", range(30))
+@pytest.mark.parametrize("mode", [W_UNIFORM, W_LOGDEPTH])
+def test_tiny_trees_match_oracle(seed, mode):
+    V = 5 + seed % 4
+    blank = 0 if seed % 2 else -1
+    toks, offs, wts = W.tiny_case(4000 + seed, vocab_size=V, blank_id=blank, max_phrases=9, max_len=6)
+    unk = 0.5 if seed % 3 == 0 else 0.0
+    fzb = seed % 5 != 0
+    ot, tr = _both(toks, offs, V, blank, weights=wts, weight_mode=mode, unk_score=unk, final_zero_backoff=fzb)
+    _compare_trees(ot, tr)
+    h = pb.pb_host_arrays(tr)
+    sc, nx = ot.score(np.arange(ot.num_states))
+    for s in range(ot.num_states):
+        fs, fn = _rows_from_flat(h, V, blank, unk, s)
+        assert np.array_equal(fs, sc[s]) and np.array_equal(fn, nx[s])
+        assert pb.pb_state_prefix(tr, s) == ot.prefix(s)
+
+
+@pytest.mark.parametrize("idx", [1, 2])
+def test_config_trees_match_oracle(idx):
+    cfg = W.CONFIGS[idx]
+    toks, offs = W.make_phrases(cfg)
+    ot, tr = _both(toks, offs, cfg.vocab_size, cfg.blank_id)
+    _compare_trees(ot, tr)
+
+
+def test_config3_tree_rows_sampled():
+    cfg = W.CONFIGS[3]
+    toks, offs = W.make_phrases(cfg)
+    ot, tr = _both(toks, offs, cfg.vocab_size, cfg.blank_id, weight_mode=W_LOGDEPTH)
+    info = pb.pb_info(tr)
+    assert info["num_states"] == ot.num_states > 100000 and info["max_fail_chain"] >= 5
+    h = pb.pb_host_arrays(tr)
+    states = W.sample_states(ot.num_states, 64, 3)
+    sc, nx = ot.score(states)
+    for i, s in enumerate(states):
+        fs, fn = _rows_from_flat(h, cfg.vocab_size, cfg.blank_id, 0.0, int(s))
+        assert np.array_equal(fs, sc[i]) and np.array_equal(fn, nx[i])
+
+
+def test_empty_list_gives_root_only_tree():
+    tr = pb.pb_build(np.zeros(0, np.int32), np.zeros(1, np.int64), 16, 0, unk_score=0.25, device=-1)
+    info = pb.pb_info(tr)
+    assert info["num_states"] == 1 and info["num_arcs"] == 0 and info["root_degree"] == 0
+    h = pb.pb_host_arrays(tr)
+    assert np.all(h["root_score"] == np.float32(0.25)) and np.all(h["root_next"] == 0)
+
+
+@pytest.mark.parametrize("bad,code", [("empty", pb.PB_EINVAL), ("range", pb.PB_ERANGE), ("blank", pb.PB_EINVAL),
+                                      ("vocab", pb.PB_EINVAL), ("neg", pb.PB_ERANGE), ("mode", pb.PB_EINVAL),
+                                      ("blank_range", pb.PB_EINVAL), ("decreasing", pb.PB_EINVAL)])
+def test_build_error_codes(bad, code):
+    toks = np.array([1, 2, 3], np.int32)
+    offs = np.array([0, 2, 3], np.int64)
+    V, blank, mode = 8, 0, 0
+    if bad == "empty":
+        offs = np.array([0, 2, 2, 3], np.int64)
+    elif bad == "range":
+        toks = np.array([1, 9, 3], np.int32)
+    elif bad == "blank":
+        toks = np.array([1, 0, 3], np.int32)
+    elif bad == "vocab":
+        V = 0
+    elif bad == "neg":
+        toks = np.array([1, -2, 3], np.int32)
+    elif bad == "mode":
+        mode = 7
+    elif bad == "blank_range":
+        blank = 8
+    elif bad == "decreasing":
+        offs = np.array([0, 2, 1], np.int64)
+    with pytest.raises(pb.PbError) as e:
+        pb.pb_build(toks, offs, V, blank, weight_mode=mode, device=-1)
+    assert e.value.code == code
+
+
+def test_step_calls_on_host_only_tree_are_rejected_not_crashing():
+    tr = pb.pb_build(np.array([1, 2], np.int32), np.array([0, 2], np.int64), 8, 0, device=-1)
+    for call in (lambda: pb.pb_score(tr, 0, 1, 0),
+                 lambda: pb.pb_fuse_step(tr, 0, 8, 0, 0.5, 1, 0, 0, 0),
+                 lambda: pb.pb_fuse_frames(tr, 0, 8, 8, 0, 0.5, 1, 1, 0, 0, 0),
+                 lambda: pb.pb_fuse_step_beam(tr, 0, 8, 0, 0, 0.5, 1, 1, 0, 0, 0, 0)):
+        with pytest.raises(pb.PbError) as e:
+            call()
+        assert e.value.code == pb.PB_EINVAL
+    with pytest.raises(pb.PbError):
+        pb.pb_state_prefix(tr, 99)
+    assert pb.strerror(pb.PB_EUNSUPPORTED) == "unsupported size" and pb.strerror(0) == "ok"
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "pb.h")).read()
+    declared = sorted(set(re.findall(r"\b(pb_[a-z_]+)\s*\(", header)))
+    assert declared == sorted(pb.EXPORTS)
+    lib = C.CDLL(pb.library_path())
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_struct_layouts_match_header_field_order():
+    header = open(os.path.join(ROOT, "include", "pb.h")).read()
+    body = re.search(r"typedef struct \{(.*?)\} pb_build_opts;", header, re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"(?:int32_t|float)\s+(\w+);", body)
+    assert fields == [n for n, _ in pb.binding.pb_build_opts._fields_]
+    body = re.search(r"typedef struct \{((?:(?!typedef struct).)*?)\} pb_tree_info;", header, re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"(?:int32_t|int64_t)\s+(\w+);", body)
+    assert fields == [n for n, _ in pb.binding.pb_tree_info._fields_]
