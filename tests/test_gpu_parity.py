@@ -43,8 +43,10 @@ def config_trees(idx, mode=W_UNIFORM):
 
 def assert_scores(got, want):
     assert got.shape == want.shape
-    assert np.all(np.abs(got.astype(np.float64) - want.astype(np.float64)) <= TOL), \
-        float(np.max(np.abs(got.astype(np.float64) - want.astype(np.float64))))
+    fin = np.isfinite(want)
+    assert np.array_equal(got[~fin], want[~fin])          # -inf (dead beams) must match exactly
+    err = np.abs(got[fin].astype(np.float64) - want[fin].astype(np.float64))
+    assert err.size == 0 or err.max() <= TOL, float(err.max())
 
 
 # ---------------------------------------------------------------------------------------- pb_score
