@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libpb.so")
-SOURCES = ["pb_compile.cpp", "pb_kernels.hip", "pb_api.hip"]
+SOURCES = ["pb_compile.cpp", "pb_kernels.hip", "pb_frames.hip", "pb_api.hip"]
 HEADERS = ["pb_tree.hpp", "pb_kernels.hpp", os.path.join(ROOT, "include", "pb.h")]
 
 

@@ -22,7 +22,8 @@ int upload(pb_tree* tr, int device) {
   const size_t n_arc = h.arc.size() * sizeof(pb::ArcRec);
   const size_t n_rs = h.root_score.size() * sizeof(float);
   const size_t n_rn = h.root_next.size() * sizeof(int32_t);
-  const size_t total = padded(n_state) + padded(n_arc) + padded(n_rs) + padded(n_rn);
+  const size_t n_pr = h.p_root.size() * sizeof(float);
+  const size_t total = padded(n_state) + padded(n_arc) + padded(n_rs) + padded(n_rn) + padded(n_pr);
   int prev = 0;
   if (hipGetDevice(&prev) != hipSuccess) { (void)hipGetLastError(); return PB_EHIP; }
   if (hipSetDevice(device) != hipSuccess) { (void)hipGetLastError(); return PB_EHIP; }
@@ -43,6 +44,8 @@ int upload(pb_tree* tr, int device) {
     tr->dev.arc = static_cast<const pb::ArcRec*>(put(h.arc.data(), n_arc));
     tr->dev.root_score = static_cast<const float*>(put(h.root_score.data(), n_rs));
     tr->dev.root_next = static_cast<const int32_t*>(put(h.root_next.data(), n_rn));
+    tr->dev.p_root = static_cast<const float*>(put(h.p_root.data(), n_pr));
+    if (rc == PB_OK) rc = pb::prepare_wave_kernels();
     tr->dev.num_states = static_cast<int32_t>(h.state.size());
     tr->dev.vocab_size = h.vocab_size;
     tr->dev.blank_id = h.blank_id;
@@ -158,6 +161,9 @@ int pb_fuse_step(const pb_tree* tree, const float* d_logp, int64_t row_stride, c
   if (B == 0) return PB_OK;
   if (!d_logp || !d_states_in || !d_tokens || !d_states_out || !d_scores) return PB_EINVAL;
   if (row_stride < tree->dev.vocab_size) return PB_EINVAL;
+  if (pb::wave_path_ok(tree->dev, d_logp, 0, row_stride))
+    return pb::launch_step_wave(tree->dev, d_logp, row_stride, d_states_in, alpha, B, d_tokens, d_states_out, d_scores,
+                                static_cast<hipStream_t>(hip_stream));
   return pb::launch_fuse(tree->dev, d_logp, 0, row_stride, d_states_in, alpha, 1, B, d_tokens, d_states_out,
                          d_scores, static_cast<hipStream_t>(hip_stream));
 }
@@ -169,6 +175,9 @@ int pb_fuse_frames(const pb_tree* tree, const float* d_logp, int64_t frame_strid
   if (B == 0 || T == 0) return PB_OK;
   if (!d_logp || !d_states0 || !d_tokens || !d_states || !d_scores) return PB_EINVAL;
   if (row_stride < tree->dev.vocab_size || frame_stride < 0) return PB_EINVAL;
+  if (pb::wave_path_ok(tree->dev, d_logp, frame_stride, row_stride))
+    return pb::launch_frames_wave(tree->dev, d_logp, frame_stride, row_stride, d_states0, alpha, T, B, d_tokens,
+                                  d_states, d_scores, static_cast<hipStream_t>(hip_stream));
   return pb::launch_fuse(tree->dev, d_logp, frame_stride, row_stride, d_states0, alpha, T, B, d_tokens, d_states,
                          d_scores, static_cast<hipStream_t>(hip_stream));
 }

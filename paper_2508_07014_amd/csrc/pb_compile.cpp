@@ -158,6 +158,13 @@ int compile_tree(const int32_t* tokens, const int64_t* offsets, int64_t n_phrase
       hops[s] = hops[t.fail[s]] + 1;
       t.max_fail_chain = std::max(t.max_fail_chain, hops[s]);
     }
+    // total backoff of each state's failure chain, summed in fp32 in the order a query pays it
+    t.p_root.assign(N, 0.0f);
+    for (int32_t s = 1; s < N; ++s) {
+      float p = 0.0f;
+      for (int32_t x = s; x != 0; x = t.fail[x]) p = p + t.backoff[x];
+      t.p_root[s] = p;
+    }
     t.root_score.assign(V, o.unk_score);
     t.root_next.assign(V, 0);
     t.root_degree = t.arc_count[0];

@@ -17,6 +17,19 @@ int launch_fuse(const DeviceTree& t, const float* d_logp, int64_t frame_stride, 
                 const int32_t* d_states0, float alpha, int32_t T, int32_t B, int32_t* d_tokens, int32_t* d_states,
                 float* d_scores, hipStream_t stream);
 
+// Wave-per-hypothesis greedy kernels (pb_frames.hip); usable when rows are 16-byte aligned and V % 4 == 0.
+constexpr int kTargetChains = 4096;  // concurrent decode chains aimed for by the multi-frame decoder
+constexpr int kMinSegLen = 8;        // shortest speculative segment, in frames
+
+bool wave_path_ok(const DeviceTree& t, const float* d_logp, int64_t frame_stride, int64_t row_stride);
+int prepare_wave_kernels();  // once per device, after the device has been made current
+int launch_step_wave(const DeviceTree& t, const float* d_logp, int64_t row_stride, const int32_t* d_states_in,
+                     float alpha, int32_t B, int32_t* d_tokens, int32_t* d_states_out, float* d_scores,
+                     hipStream_t stream);
+int launch_frames_wave(const DeviceTree& t, const float* d_logp, int64_t frame_stride, int64_t row_stride,
+                       const int32_t* d_states0, float alpha, int32_t T, int32_t B, int32_t* d_tokens,
+                       int32_t* d_states, float* d_scores, hipStream_t stream);
+
 int launch_beam(const DeviceTree& t, const float* d_logp, int64_t row_stride, const float* d_hyp,
                 const int32_t* d_states_in, float alpha, int32_t U, int32_t K, int32_t* d_tokens, int32_t* d_parents,
                 int32_t* d_states_out, float* d_scores_out, hipStream_t stream);

@@ -27,6 +27,7 @@ struct DeviceTree {
   const ArcRec* arc = nullptr;      // [N-1]
   const float* root_score = nullptr;  // [V]
   const int32_t* root_next = nullptr;  // [V]
+  const float* p_root = nullptr;       // [N] backoff accumulated from the state down to the root (fp32, chain order)
   int32_t num_states = 0;
   int32_t vocab_size = 0;
   int32_t blank_id = -1;
@@ -38,7 +39,7 @@ struct HostTree {
   std::vector<StateRec> state;
   std::vector<ArcRec> arc;
   std::vector<int32_t> arc_begin, arc_count, fail, depth, parent, arc_token, root_next;
-  std::vector<float> backoff, arc_score, root_score;
+  std::vector<float> backoff, arc_score, root_score, p_root;
   std::vector<uint8_t> is_final;
   std::vector<double> acc;
 };
