@@ -23,7 +23,8 @@ int upload(pb_tree* tr, int device) {
   const size_t n_rs = h.root_score.size() * sizeof(float);
   const size_t n_rn = h.root_next.size() * sizeof(int32_t);
   const size_t n_pr = h.p_root.size() * sizeof(float);
-  const size_t total = padded(n_state) + padded(n_arc) + padded(n_rs) + padded(n_rn) + padded(n_pr);
+  const size_t n_rr = h.root_rec.size() * sizeof(pb::RootRec);
+  const size_t total = padded(n_state) + padded(n_arc) + padded(n_rs) + padded(n_rn) + padded(n_pr) + padded(n_rr);
   int prev = 0;
   if (hipGetDevice(&prev) != hipSuccess) { (void)hipGetLastError(); return PB_EHIP; }
   if (hipSetDevice(device) != hipSuccess) { (void)hipGetLastError(); return PB_EHIP; }
@@ -45,6 +46,7 @@ int upload(pb_tree* tr, int device) {
     tr->dev.root_score = static_cast<const float*>(put(h.root_score.data(), n_rs));
     tr->dev.root_next = static_cast<const int32_t*>(put(h.root_next.data(), n_rn));
     tr->dev.p_root = static_cast<const float*>(put(h.p_root.data(), n_pr));
+    tr->dev.root_rec = static_cast<const pb::RootRec*>(put(h.root_rec.data(), n_rr));
     if (rc == PB_OK) rc = pb::prepare_wave_kernels();
     tr->dev.num_states = static_cast<int32_t>(h.state.size());
     tr->dev.vocab_size = h.vocab_size;

@@ -174,6 +174,11 @@ int compile_tree(const int32_t* tokens, const int64_t* offsets, int64_t n_phrase
     }
     t.state.resize(N);
     for (int32_t s = 0; s < N; ++s) t.state[s] = {t.arc_begin[s], t.arc_count[s], t.fail[s], t.backoff[s]};
+    t.root_rec.resize(V);
+    for (int32_t v = 0; v < V; ++v) {
+      const int32_t n = t.root_next[v];
+      t.root_rec[v] = {n, t.arc_begin[n], t.arc_count[n], t.fail[n], t.backoff[n], t.p_root[n], 0, 0};
+    }
     t.arc.resize(t.arc_token.size());
     for (size_t j = 0; j < t.arc.size(); ++j) t.arc[j] = {t.arc_token[j], t.arc_score[j]};
     out = std::move(t);

@@ -9,13 +9,17 @@
 //    p_root + root_score[v] (all backoffs down to the root, then the root arc or the c_unk
 //    self-loop).  alpha * that is cached per lane while p_root does not change, so the common
 //    frame costs one add and a max per token.  The row max is reduced with DPP on order-preserving
-//    integer keys; the winner is the lowest token index holding that value (fp32 compare).
+//    unsigned keys; the winner is the lowest token index holding that value (fp32 compare), found
+//    with ballots over the four 256-token groups.
 //  * Arc candidates.  The failure chain is walked with scalar loads (the state is wave-uniform);
 //    at each chain state the lanes take one arc each, gather its log-prob from the LDS copy of the
-//    row and evaluate Eq. 1 for it.  A per-token LDS tag written with a per-(frame, chunk) stamp
-//    marks overridden tokens: it hides arcs shadowed by a deeper chain state and tells whether the
-//    base winner is itself overridden.  Only in that last case (and only if the arcs do not beat it
-//    anyway) a second pass recomputes the base winner without the overridden tokens.
+//    row and evaluate Eq. 1 for it.  Chains with more than one state stamp a per-token LDS tag so
+//    that an arc shadowed by a deeper chain state is skipped.  If the base winner is itself an
+//    overridden token and the arcs do not beat it, a second pass recomputes the base winner
+//    without the overridden tokens.
+//  * The record of the next state (arc range, failure link, backoffs) is fetched with the lookup
+//    that yields the state: a dense per-token table holds it for the base winner and is read as
+//    soon as that winner is known, before the arcs have been evaluated.
 //  * Multi-frame decoding splits the T frames of a hypothesis into segments decoded concurrently,
 //    every segment but the first speculatively from the root state.  The decoder is a finite
 //    automaton step, so a re-run from the true start state needs to go only as far as the frame
@@ -28,6 +32,7 @@
 #include <climits>
 #include <cmath>
 #include <cstdint>
+#include <cstdlib>
 
 #include "pb_kernels.hpp"
 
@@ -39,14 +44,17 @@ namespace {
 
 constexpr int kChunk = 1024;  // tokens per chunk: 16 per lane
 
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+using u64 = unsigned long long;
+
 // Scalar-load views: the tree is never written while kernels run, so wave-uniform reads may go
 // through the constant address space (scalar cache).
-typedef int v4i __attribute__((ext_vector_type(4)));
-
 struct TreeView {
-  const v4i PB_AS4* state;  // StateRec as four dwords: arc_begin, arc_count, fail, backoff bits
+  const v4i PB_AS4* state;     // StateRec as four dwords: arc_begin, arc_count, fail, backoff bits
   const float PB_AS4* p_root;
   const int32_t PB_AS4* root_next;
+  const v8i PB_AS4* root_rec;  // RootRec as eight dwords
   const ArcRec* arc;
   const float* root_score;
   int num_states, V, blank;
@@ -57,6 +65,7 @@ __device__ __forceinline__ TreeView make_view(const DeviceTree& t) {
   v.state = (const v4i PB_AS4*)t.state;
   v.p_root = (const float PB_AS4*)t.p_root;
   v.root_next = (const int32_t PB_AS4*)t.root_next;
+  v.root_rec = (const v8i PB_AS4*)t.root_rec;
   v.arc = t.arc;
   v.root_score = t.root_score;
   v.num_states = t.num_states;
@@ -65,120 +74,372 @@ __device__ __forceinline__ TreeView make_view(const DeviceTree& t) {
   return v;
 }
 
-__device__ __forceinline__ int key_of(float f) {  // order-preserving fp32 -> int32 (an involution)
-  const int b = __float_as_int(f);
-  return b ^ ((b >> 31) & 0x7fffffff);
+// Values that are wave-uniform by construction, told to the compiler (keeps them in SGPRs and the
+// loads they address on the scalar path).
+__device__ __forceinline__ int uniform_i(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ float uniform_f(float v) {
+  return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v)));
 }
-__device__ __forceinline__ float val_of(int k) { return __int_as_float(k ^ ((k >> 31) & 0x7fffffff)); }
+
+// Order-preserving fp32 <-> uint32 (every real value, -inf included, maps above 0).
+__device__ __forceinline__ unsigned ukey(float f) {
+  const int b = __float_as_int(f);
+  return static_cast<unsigned>(b) ^ (static_cast<unsigned>(b >> 31) | 0x80000000u);
+}
+__device__ __forceinline__ float ukey_val(unsigned k) {
+  const unsigned m = (k & 0x80000000u) ? 0x80000000u : 0xffffffffu;
+  return __uint_as_float(k ^ m);
+}
 
 template <int CTRL>
-__device__ __forceinline__ int dpp(int v) {
-  return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
+__device__ __forceinline__ unsigned dpp0(unsigned v) {  // lanes without a source read 0
+  return static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xf, 0xf, true));
 }
-// Wave-wide max / min of an int; the result is wave-uniform (read from lane 63).
-__device__ __forceinline__ int wave_max_i(int v) {
-  v = max(v, dpp<0x111>(v));  // row_shr:1
-  v = max(v, dpp<0x112>(v));  // row_shr:2
-  v = max(v, dpp<0x114>(v));  // row_shr:4
-  v = max(v, dpp<0x118>(v));  // row_shr:8
-  v = max(v, dpp<0x142>(v));  // row_bcast:15
-  v = max(v, dpp<0x143>(v));  // row_bcast:31
-  return __builtin_amdgcn_readlane(v, 63);
+// Wave-wide unsigned max; 0 is the identity.  The result is wave-uniform (read from lane 63).
+__device__ __forceinline__ unsigned wave_max_u(unsigned v) {
+  v = max(v, dpp0<0x111>(v));  // row_shr:1
+  v = max(v, dpp0<0x112>(v));  // row_shr:2
+  v = max(v, dpp0<0x114>(v));  // row_shr:4
+  v = max(v, dpp0<0x118>(v));  // row_shr:8
+  v = max(v, dpp0<0x142>(v));  // row_bcast:15
+  v = max(v, dpp0<0x143>(v));  // row_bcast:31
+  return static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(v), 63));
 }
-__device__ __forceinline__ int wave_min_i(int v) {
-  v = min(v, dpp<0x111>(v));
-  v = min(v, dpp<0x112>(v));
-  v = min(v, dpp<0x114>(v));
-  v = min(v, dpp<0x118>(v));
-  v = min(v, dpp<0x142>(v));
-  v = min(v, dpp<0x143>(v));
-  return __builtin_amdgcn_readlane(v, 63);
+// Wave-wide min of non-negative ints (INT_MAX = nothing).
+__device__ __forceinline__ int wave_min_nn(int v) {
+  return INT_MAX - static_cast<int>(wave_max_u(static_cast<unsigned>(INT_MAX - v)));
 }
+__device__ __forceinline__ int first_lane(u64 mask) { return __builtin_ctzll(mask); }
 
 __device__ __forceinline__ int tok_of(int j, int lane) { return 256 * (j >> 2) + 4 * lane + (j & 3); }
 
+__device__ __forceinline__ bool valid_state(const TreeView& t, int s) {
+  return static_cast<unsigned>(s) < static_cast<unsigned>(t.num_states);
+}
+
+struct Rec {  // wave-uniform copy of a StateRec
+  int begin, count, fail;
+  float backoff;
+};
+__device__ __forceinline__ Rec load_rec(const TreeView& t, int s) {
+  const v4i r = t.state[s];
+  Rec o;
+  o.begin = r.x;
+  o.count = r.y;
+  o.fail = r.z;
+  o.backoff = __int_as_float(r.w);
+  return o;
+}
+
+struct Cursor {  // wave-uniform decoding state of one hypothesis
+  int s;
+  Rec rec;
+  float p_root;
+};
+__device__ __forceinline__ Cursor cursor_at(const TreeView& t, int s) {
+  Cursor c;
+  c.s = s;
+  c.rec = load_rec(t, s);
+  c.p_root = t.p_root[s];
+  return c;
+}
+__device__ __forceinline__ Cursor cursor_from_root_rec(const v8i& r) {
+  Cursor c;
+  c.s = r.s0;
+  c.rec.begin = r.s1;
+  c.rec.count = r.s2;
+  c.rec.fail = r.s3;
+  c.rec.backoff = __int_as_float(r.s4);
+  c.p_root = __int_as_float(r.s5);
+  return c;
+}
+
+// alpha * (p_root + root_score[v]) for the lane's 16 tokens; the blank column boosts by 0.
+__device__ __forceinline__ void make_base_boost(int cb, int lane, int blank, float p_root, float alpha,
+                                                const float (&rw)[16], float (&c)[16]) {
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    const float boost = (cb + tok_of(j, lane) == blank) ? 0.0f : __fadd_rn(p_root, rw[j]);
+    c[j] = __fmul_rn(alpha, boost);
+  }
+}
+
+// Loads the lane's 16 values of chunk `cb` of a V-long fp32 array; positions >= V read as `fill`.
+template <bool FULL>
+__device__ __forceinline__ void load16(const float* __restrict__ base, int cb, int V, int lane, float fill,
+                                       float (&x)[16]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int v = cb + 256 * i + 4 * lane;
+    if (FULL || v < V) {  // V % 4 == 0: a 16-byte group is entirely inside or outside the row
+      const float4 q = *reinterpret_cast<const float4*>(base + v);
+      x[4 * i + 0] = q.x; x[4 * i + 1] = q.y; x[4 * i + 2] = q.z; x[4 * i + 3] = q.w;
+    } else {
+      x[4 * i + 0] = x[4 * i + 1] = x[4 * i + 2] = x[4 * i + 3] = fill;
+    }
+  }
+}
+
+__device__ __forceinline__ void store_row_lds(float* row, int lane, const float (&x)[16]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    *reinterpret_cast<float4*>(row + 256 * i + 4 * lane) = make_float4(x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]);
+}
+
+// Lowest token (chunk-relative) whose fused value equals M; g are the lane's four group maxima.
+__device__ __forceinline__ int first_token_equal(const float (&f)[16], const float (&g)[4], float M, int lane) {
+  const u64 b0 = __ballot(g[0] == M), b1 = __ballot(g[1] == M), b2 = __ballot(g[2] == M), b3 = __ballot(g[3] == M);
+  int gi;
+  u64 bm, e0, e1, e2, e3;
+  if (b0) {
+    gi = 0; bm = b0;
+    e0 = __ballot(f[0] == M); e1 = __ballot(f[1] == M); e2 = __ballot(f[2] == M); e3 = __ballot(f[3] == M);
+  } else if (b1) {
+    gi = 1; bm = b1;
+    e0 = __ballot(f[4] == M); e1 = __ballot(f[5] == M); e2 = __ballot(f[6] == M); e3 = __ballot(f[7] == M);
+  } else if (b2) {
+    gi = 2; bm = b2;
+    e0 = __ballot(f[8] == M); e1 = __ballot(f[9] == M); e2 = __ballot(f[10] == M); e3 = __ballot(f[11] == M);
+  } else if (b3) {
+    gi = 3; bm = b3;
+    e0 = __ballot(f[12] == M); e1 = __ballot(f[13] == M); e2 = __ballot(f[14] == M); e3 = __ballot(f[15] == M);
+  } else {
+    return 0;  // only with NaN inputs (precondition violation): stay in range
+  }
+  const int L = first_lane(bm);
+  const u64 bit = 1ull << L;
+  const int k = (e0 & bit) ? 0 : (e1 & bit) ? 1 : (e2 & bit) ? 2 : 3;
+  return 256 * gi + 4 * L + k;
+}
+
+// ------------------------------------------------------------------------------------------------
+// One frame of a row with V <= 1024 (a single chunk).  `cur` is the hypothesis' state with its
+// record; on return it is the state after the chosen token.  Returns the token and fused value.
+//   x    lane's raw log-probs (registers);  c / c_p  cached base boosts and the p_root they are for
+//   rw   lane's root scores;  row / tag  this wave's LDS row copy and tags;  stamp  tag stamp counter
+template <typename Hook>
+__device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const float (&x)[16], float (&c)[16],
+                                         float& c_p, const float (&rw)[16], float alpha, float* row, unsigned* tag,
+                                         unsigned& stamp, int lane, Hook&& after_arcs, float& out_val, int& out_tok) {
+  const int s = cur.s;
+  const Rec rec0 = cur.rec;
+  if (__float_as_int(c_p) != __float_as_int(cur.p_root)) {
+    make_base_boost(0, lane, t.blank, cur.p_root, alpha, rw, c);
+    c_p = cur.p_root;
+  }
+  // ---- early load: record of the next chain state ------------------------------------------------
+  const bool chain = (s != 0);
+  const bool multi = chain && rec0.fail != 0;
+  Rec nrec = rec0;
+  if (multi) nrec = load_rec(t, rec0.fail);
+
+  // ---- base candidates ---------------------------------------------------------------------------
+  float f[16], g[4];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) f[j] = __fadd_rn(x[j], c[j]);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) g[i] = fmaxf(fmaxf(f[4 * i], f[4 * i + 1]), fmaxf(f[4 * i + 2], f[4 * i + 3]));
+  const float M = ukey_val(wave_max_u(ukey(fmaxf(fmaxf(g[0], g[1]), fmaxf(g[2], g[3])))));
+  const int vb = first_token_equal(f, g, M, lane);
+  const v8i rr = t.root_rec[vb];  // record of the state the base winner leads to (speculative)
+
+  // ---- arc candidates along the failure chain ----------------------------------------------------
+  float bf = -INFINITY;
+  int btok = INT_MAX, bchild = 0;
+  bool hit_vb = false;
+  if (chain) {
+    store_row_lds(row, lane, x);
+    unsigned st = 0;
+    if (multi) st = ++stamp;
+    Rec r = rec0;
+    float p = 0.0f;
+    int level = 0;
+    for (;;) {
+      for (int j0 = 0; j0 < r.count; j0 += 64) {
+        // every lane loads (the index is clamped into the row) so that the load and its use stay
+        // in one block; lanes past the end of the row are discarded by `valid`
+        const bool valid = j0 + lane < r.count;
+        const int j = min(j0 + lane, r.count - 1);
+        const ArcRec a = t.arc[r.begin + j];
+        const int tk = a.token;
+        bool shadowed = !valid;
+        if (multi) {
+          if (level > 0) shadowed = shadowed || (tag[tk] == st);  // a deeper chain state owns this token
+          if (valid) tag[tk] = st;
+        }
+        hit_vb = hit_vb || (valid && tk == vb);
+        const float fa = __fadd_rn(row[tk], __fmul_rn(alpha, __fadd_rn(p, a.score)));
+        if (!shadowed && (fa > bf || (fa == bf && tk < btok))) {
+          bf = fa;
+          btok = tk;
+          bchild = r.begin + j + 1;
+        }
+      }
+      p = __fadd_rn(p, r.backoff);
+      if (r.fail == 0) break;
+      r = nrec;
+      if (r.fail != 0) nrec = load_rec(t, r.fail);
+      ++level;
+    }
+  }
+  after_arcs();
+
+  // ---- decision -----------------------------------------------------------------------------------
+  bool arc_wins = false;
+  int va = INT_MAX, achild = 0;
+  float MA = 0.0f;
+  float base_val = M;
+  int base_tok = vb;
+  const bool mine0 = btok != INT_MAX;
+  if (__ballot(mine0) != 0) {
+    MA = ukey_val(wave_max_u(mine0 ? ukey(bf) : 0u));
+    const bool mine = mine0 && bf == MA;
+    const u64 eq = __ballot(mine);
+    if ((eq & (eq - 1)) == 0) {  // one lane holds the maximum
+      const int L = first_lane(eq);
+      va = __builtin_amdgcn_readlane(btok, L);
+      achild = __builtin_amdgcn_readlane(bchild, L);
+    } else {
+      va = wave_min_nn(mine ? btok : INT_MAX);
+      achild = __builtin_amdgcn_readlane(bchild, first_lane(__ballot(mine && btok == va)));
+    }
+    const bool vb_overridden = __ballot(hit_vb) != 0;
+    if (MA > M) {
+      arc_wins = true;
+    } else if (!vb_overridden) {
+      arc_wins = (MA == M) && (va < vb);
+    } else {
+      // The base winner is shadowed by an arc that does not beat it: tag every overridden token and
+      // redo the base arg-max without them.
+      const unsigned st2 = ++stamp;
+      for (int xs = s; xs != 0;) {
+        const Rec r = load_rec(t, xs);
+        for (int j = lane; j < r.count; j += 64) tag[t.arc[r.begin + j].token] = st2;
+        xs = uniform_i(r.fail);
+      }
+      unsigned k[16], mk = 0u;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        k[j] = (tag[tok_of(j, lane)] == st2) ? 0u : ukey(f[j]);
+        mk = max(mk, k[j]);
+      }
+      const unsigned Mk = wave_max_u(mk);
+      bool have_base = Mk != 0u;
+      if (have_base) {
+        base_val = ukey_val(Mk);
+        int l2 = INT_MAX;
+#pragma unroll
+        for (int j = 15; j >= 0; --j) l2 = (k[j] != 0u && f[j] == base_val) ? tok_of(j, lane) : l2;
+        base_tok = wave_min_nn(l2);
+        have_base = base_tok != INT_MAX;
+      }
+      arc_wins = !have_base || MA > base_val || (MA == base_val && va < base_tok);
+    }
+  }
+  if (arc_wins) {
+    out_val = MA;
+    out_tok = va;
+    cur = cursor_at(t, achild);
+  } else {
+    out_val = base_val;
+    out_tok = base_tok;
+    if (base_tok != t.blank) {  // the blank keeps the state
+      if (base_tok == vb) {
+        cur = cursor_from_root_rec(rr);
+      } else {
+        const v8i r2 = t.root_rec[base_tok];
+        cur = cursor_from_root_rec(r2);
+      }
+    }
+  }
+  cur.s = uniform_i(cur.s);
+  cur.rec.begin = uniform_i(cur.rec.begin);
+  cur.rec.count = uniform_i(cur.rec.count);
+  cur.rec.fail = uniform_i(cur.rec.fail);
+  cur.rec.backoff = uniform_f(cur.rec.backoff);
+  cur.p_root = uniform_f(cur.p_root);
+  out_val = uniform_f(out_val);
+  out_tok = uniform_i(out_tok);
+}
+
+// Decodes frames [f0, f1) of hypothesis b (V <= 1024) starting in valid state s.  With COMPARE set,
+// stops after the first frame whose out-state equals the one already stored in `states` (the
+// stored trajectory is then valid from there on).
+template <bool COMPARE, bool FULL>
+__device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
+                                              int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s,
+                                              int32_t* __restrict__ tokens, int32_t* __restrict__ states,
+                                              float* __restrict__ scores, float* row, unsigned* tag, unsigned& stamp,
+                                              int lane) {
+  const int V = t.V;
+  const float* rp = logp + static_cast<size_t>(b) * row_stride + static_cast<size_t>(f0) * frame_stride;
+  float buf[3][16], rw[16], c[16];
+  if (f0 < f1) load16<FULL>(rp, 0, V, lane, -INFINITY, buf[0]);
+  if (f0 + 1 < f1) load16<FULL>(rp + frame_stride, 0, V, lane, -INFINITY, buf[1]);
+  load16<FULL>(t.root_score, 0, V, lane, 0.0f, rw);
+  Cursor cur = cursor_at(t, s);
+  float c_p = cur.p_root;
+  make_base_boost(0, lane, t.blank, c_p, alpha, rw, c);
+  size_t o = static_cast<size_t>(f0) * B + b;
+  bool stop = false;
+  for (int fb = f0; fb < f1 && !stop; fb += 3) {
+#pragma unroll
+    for (int u = 0; u < 3; ++u) {
+      const int f = fb + u;
+      if (f < f1 && !stop) {
+        float val;
+        int tok;
+        frame_1k(t, cur, buf[u], c, c_p, rw, alpha, row, tag, stamp, lane,
+                 [&]() {
+                   if (f + 2 < f1) load16<FULL>(rp + 2 * frame_stride, 0, V, lane, -INFINITY, buf[(u + 2) % 3]);
+                 },
+                 val, tok);
+        int stored = 0;
+        if (COMPARE) stored = uniform_i(__hip_atomic_load(states + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        if (lane == 0) {
+          tokens[o] = tok;
+          states[o] = cur.s;
+          scores[o] = val;
+        }
+        if (COMPARE && stored == cur.s) stop = true;
+        rp += frame_stride;
+        o += B;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Rows longer than 1024 tokens: the same scheme chunk by chunk (tags used for every arc).
 struct Win {  // wave-uniform result of one chunk or frame
   float val;
   int tok;
   int next;
 };
 
-// Loads the lane's 16 log-probs of chunk `cb` (token base) of a row; tokens >= V read as -inf.
-__device__ __forceinline__ void load_chunk(const float* __restrict__ lrow, int cb, int V, int lane, float (&x)[16]) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int v = cb + 256 * i + 4 * lane;
-    if (v < V) {  // V % 4 == 0: a 16-byte group is entirely inside or outside the row
-      const float4 q = *reinterpret_cast<const float4*>(lrow + v);
-      x[4 * i + 0] = q.x; x[4 * i + 1] = q.y; x[4 * i + 2] = q.z; x[4 * i + 3] = q.w;
-    } else {
-      x[4 * i + 0] = x[4 * i + 1] = x[4 * i + 2] = x[4 * i + 3] = -INFINITY;
-    }
-  }
-}
-
-// alpha * (p_root + root_score[v]) for the lane's tokens of a chunk; the blank column boosts by 0.
-__device__ __forceinline__ void make_base_boost(const TreeView& t, int cb, int lane, float p_root, float alpha,
-                                                float (&c)[16]) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int v = cb + 256 * i + 4 * lane;
-    float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (v < t.V) r = *reinterpret_cast<const float4*>(t.root_score + v);
-    const float rs[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const float boost = (v + k == t.blank) ? 0.0f : __fadd_rn(p_root, rs[k]);
-      c[4 * i + k] = __fmul_rn(alpha, boost);
-    }
-  }
-}
-
-// One chunk of one row for a valid state s: the best token of the chunk by (fused value descending,
-// token ascending), its fused value and the state it leads to.
-//   x      lane's raw log-probs of the chunk (registers)
-//   c      lane's base boosts for (s, chunk) (registers)
-//   row    this wave's LDS copy of the chunk (written here when the state has a chain)
-//   tag    this wave's LDS tags; `stamp` must be unique per call
-template <typename AfterArcs>
 __device__ __forceinline__ Win decide_chunk(const TreeView& t, int s, int cb, const float (&x)[16], const float (&c)[16],
-                                            float alpha, float* row, unsigned* tag, unsigned stamp, int lane,
-                                            AfterArcs&& after_arcs) {
-  // ---- base candidates ---------------------------------------------------------------------------
-  float f[16];
+                                            float alpha, float* row, unsigned* tag, unsigned stamp, int lane) {
+  float f[16], g[4];
 #pragma unroll
   for (int j = 0; j < 16; ++j) f[j] = __fadd_rn(x[j], c[j]);
-  float m = f[0];
 #pragma unroll
-  for (int j = 1; j < 16; ++j) m = fmaxf(m, f[j]);
-  const float M = val_of(wave_max_i(key_of(m)));
-  int loc = INT_MAX;
-#pragma unroll
-  for (int j = 15; j >= 0; --j) loc = (f[j] == M) ? tok_of(j, lane) : loc;
-  int vb = wave_min_i(loc);
-  if (vb == INT_MAX) vb = 0;  // only with NaN inputs (precondition violation): stay in range
+  for (int i = 0; i < 4; ++i) g[i] = fmaxf(fmaxf(f[4 * i], f[4 * i + 1]), fmaxf(f[4 * i + 2], f[4 * i + 3]));
+  const float M = ukey_val(wave_max_u(ukey(fmaxf(fmaxf(g[0], g[1]), fmaxf(g[2], g[3])))));
+  const int vb = first_token_equal(f, g, M, lane);
 
-  // ---- arc candidates along the failure chain ----------------------------------------------------
   bool have_arcs = false;
-  float bf = 0.0f;
-  int bk = INT_MIN, btok = INT_MAX, bchild = 0;
+  float bf = -INFINITY;
+  int btok = INT_MAX, bchild = 0;
   if (s != 0) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      *reinterpret_cast<float4*>(row + 256 * i + 4 * lane) = make_float4(x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]);
+    store_row_lds(row, lane, x);
     float p = 0.0f;
     int xs = s, level = 0;
     while (xs != 0) {
-      const v4i raw = t.state[xs];
-      StateRec r;
-      r.arc_begin = raw.x;
-      r.arc_count = raw.y;
-      r.fail = raw.z;
-      r.backoff = __int_as_float(raw.w);
-      for (int j0 = 0; j0 < r.arc_count; j0 += 64) {
+      const Rec r = load_rec(t, xs);
+      for (int j0 = 0; j0 < r.count; j0 += 64) {
         const int j = j0 + lane;
-        if (j < r.arc_count) {
-          const ArcRec a = t.arc[r.arc_begin + j];
+        if (j < r.count) {
+          const ArcRec a = t.arc[r.begin + j];
           const unsigned rel = static_cast<unsigned>(a.token - cb);
           if (rel < static_cast<unsigned>(kChunk)) {
             bool shadowed = false;
@@ -186,69 +447,54 @@ __device__ __forceinline__ Win decide_chunk(const TreeView& t, int s, int cb, co
             tag[rel] = stamp;
             if (!shadowed) {
               const float fa = __fadd_rn(row[rel], __fmul_rn(alpha, __fadd_rn(p, a.score)));
-              if (bk == INT_MIN || fa > bf || (fa == bf && static_cast<int>(rel) < btok)) {
+              if (fa > bf || (fa == bf && static_cast<int>(rel) < btok)) {
                 bf = fa;
-                bk = key_of(fa);
                 btok = static_cast<int>(rel);
-                bchild = r.arc_begin + j + 1;
+                bchild = r.begin + j + 1;
               }
             }
           }
         }
       }
-      have_arcs = have_arcs || r.arc_count > 0;
+      have_arcs = have_arcs || r.count > 0;
       p = __fadd_rn(p, r.backoff);
-      xs = r.fail;
+      xs = uniform_i(r.fail);
       ++level;
     }
   }
-  after_arcs();
 
   Win w;
   bool arc_wins = false;
   int va = INT_MAX, achild = 0;
-  float MA = 0.0f;
-  bool have_cand = false;
-  if (have_arcs) {
-    const int ak = wave_max_i(bk);
-    if (ak != INT_MIN) {  // some arc fell into this chunk
-      have_cand = true;
-      MA = val_of(ak);
-      const bool mine = (bk != INT_MIN) && (bf == MA);
-      va = wave_min_i(mine ? btok : INT_MAX);
-      const unsigned long long who = __ballot(mine && btok == va);
-      achild = __builtin_amdgcn_readlane(bchild, __ffsll(static_cast<long long>(who)) - 1);
-    }
-  }
-  float base_val = M;
+  float MA = 0.0f, base_val = M;
   int base_tok = vb;
-  bool have_base = true;
-  if (have_cand) {
-    const bool vb_overridden = __builtin_amdgcn_readfirstlane(static_cast<int>(tag[vb] == stamp)) != 0;
+  const bool mine0 = btok != INT_MAX;
+  if (have_arcs && __ballot(mine0) != 0) {  // some arc fell into this chunk
+    MA = ukey_val(wave_max_u(mine0 ? ukey(bf) : 0u));
+    const bool mine = mine0 && bf == MA;
+    va = wave_min_nn(mine ? btok : INT_MAX);
+    achild = __builtin_amdgcn_readlane(bchild, first_lane(__ballot(mine && btok == va)));
+    const bool vb_overridden = uniform_i(static_cast<int>(tag[vb] == stamp)) != 0;
     if (MA > M) {
       arc_wins = true;
     } else if (!vb_overridden) {
       arc_wins = (MA == M) && (va < vb);
     } else {
-      // The base winner is shadowed by an arc that does not beat it: redo the base arg-max without
-      // the overridden tokens.
-      int k[16];
-      int mk = INT_MIN;
+      unsigned k[16], mk = 0u;
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
-        k[j] = (tag[tok_of(j, lane)] == stamp) ? INT_MIN : key_of(f[j]);
+        k[j] = (tag[tok_of(j, lane)] == stamp) ? 0u : ukey(f[j]);
         mk = max(mk, k[j]);
       }
-      const int Mk = wave_max_i(mk);
-      if (Mk == INT_MIN) {
-        have_base = false;
-      } else {
-        base_val = val_of(Mk);
+      const unsigned Mk = wave_max_u(mk);
+      bool have_base = Mk != 0u;
+      if (have_base) {
+        base_val = ukey_val(Mk);
         int l2 = INT_MAX;
 #pragma unroll
-        for (int j = 15; j >= 0; --j) l2 = (k[j] != INT_MIN && f[j] == base_val) ? tok_of(j, lane) : l2;
-        base_tok = wave_min_i(l2);
-        if (base_tok == INT_MAX) have_base = false;
+        for (int j = 15; j >= 0; --j) l2 = (k[j] != 0u && f[j] == base_val) ? tok_of(j, lane) : l2;
+        base_tok = wave_min_nn(l2);
+        have_base = base_tok != INT_MAX;
       }
       arc_wins = !have_base || MA > base_val || (MA == base_val && va < base_tok);
     }
@@ -265,74 +511,67 @@ __device__ __forceinline__ Win decide_chunk(const TreeView& t, int s, int cb, co
   return w;
 }
 
-__device__ __forceinline__ bool valid_state(const TreeView& t, int s) {
-  return static_cast<unsigned>(s) < static_cast<unsigned>(t.num_states);
-}
-
-// Decodes frames [f0, f1) of hypothesis b starting in state s (valid).  With `compare` set, stops
-// after the first frame whose out-state equals the one already stored in `states` (the stored
-// trajectory is then valid from there on).  Returns the state after the last decoded frame; *met
-// tells whether the stored trajectory was met before f1.
 template <bool COMPARE>
-__device__ __forceinline__ int run_frames(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
-                                          int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s,
-                                          int32_t* __restrict__ tokens, int32_t* __restrict__ states,
-                                          float* __restrict__ scores, float* row, unsigned* tag, unsigned& stamp,
-                                          int lane, bool* met) {
+__device__ __forceinline__ void run_frames_multi(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
+                                                 int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s,
+                                                 int32_t* __restrict__ tokens, int32_t* __restrict__ states,
+                                                 float* __restrict__ scores, float* row, unsigned* tag, unsigned& stamp,
+                                                 int lane) {
   const int V = t.V;
   const int nch = (V + kChunk - 1) / kChunk;
-  const int total = (f1 - f0) * nch;
-  const float* base_ptr = logp + static_cast<size_t>(b) * row_stride;
-  float buf[3][16];
-  float c[16];
-  float c_p = 0.0f;
-  int c_chunk = -1;  // (p_root, chunk) the cached base boosts belong to
-  auto issue = [&](int q, float (&dst)[16]) {
-    const int f = f0 + q / nch, ch = q - (q / nch) * nch;
-    load_chunk(base_ptr + static_cast<size_t>(f) * frame_stride, ch * kChunk, V, lane, dst);
-  };
-  if (total > 0) issue(0, buf[0]);
-  if (total > 1) issue(1, buf[1]);
-  Win best{0.0f, -1, s};
-  bool stop = false;
-  if (met) *met = false;
-  for (int q0 = 0; q0 < total && !stop; q0 += 3) {
+  const float* rp = logp + static_cast<size_t>(b) * row_stride + static_cast<size_t>(f0) * frame_stride;
+  size_t o = static_cast<size_t>(f0) * B + b;
+  float x[2][16], rw[16], c[16];
+  for (int f = f0; f < f1; ++f) {
+    const float p_root = uniform_f(t.p_root[s]);
+    Win best{0.0f, -1, s};
+    load16<false>(rp, 0, V, lane, -INFINITY, x[0]);
+    for (int ch0 = 0; ch0 < nch; ch0 += 2) {
 #pragma unroll
-    for (int u = 0; u < 3; ++u) {
-      const int q = q0 + u;
-      if (q < total && !stop) {
-        const int f = f0 + q / nch, ch = q - (q / nch) * nch;
-        const float p_root = t.p_root[s];
-        if (c_chunk != ch || __float_as_int(c_p) != __float_as_int(p_root)) {
-          make_base_boost(t, ch * kChunk, lane, p_root, alpha, c);
-          c_chunk = ch;
-          c_p = p_root;
-        }
-        const Win w = decide_chunk(t, s, ch * kChunk, buf[u], c, alpha, row, tag, ++stamp, lane, [&]() {
-          if (!COMPARE && q + 2 < total) issue(q + 2, buf[(u + 2) % 3]);
-        });
-        if (COMPARE && q + 2 < total) issue(q + 2, buf[(u + 2) % 3]);
-        if (best.tok < 0 || w.val > best.val) best = w;  // chunks ascend, so ties keep the lower token
-        if (ch == nch - 1) {
-          const size_t o = static_cast<size_t>(f) * B + b;
-          int stored = 0;
-          if (COMPARE) stored = states[o];
-          if (lane == 0) {
-            tokens[o] = best.tok;
-            states[o] = best.next;
-            scores[o] = best.val;
-          }
-          s = best.next;
-          best.tok = -1;
-          if (COMPARE && __builtin_amdgcn_readfirstlane(stored) == s) {
-            stop = true;
-            if (met) *met = true;
-          }
+      for (int u = 0; u < 2; ++u) {
+        const int ch = ch0 + u;
+        if (ch < nch) {
+          if (ch + 1 < nch) load16<false>(rp, (ch + 1) * kChunk, V, lane, -INFINITY, x[(u + 1) % 2]);
+          load16<false>(t.root_score, ch * kChunk, V, lane, 0.0f, rw);
+          make_base_boost(ch * kChunk, lane, t.blank, p_root, alpha, rw, c);
+          const Win w = decide_chunk(t, s, ch * kChunk, x[u], c, alpha, row, tag, ++stamp, lane);
+          if (best.tok < 0 || w.val > best.val) best = w;  // chunks ascend, so ties keep the lower token
+          best.val = uniform_f(best.val);
+          best.tok = uniform_i(best.tok);
+          best.next = uniform_i(best.next);
         }
       }
     }
+    int stored = 0;
+    if (COMPARE) stored = uniform_i(__hip_atomic_load(states + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    if (lane == 0) {
+      tokens[o] = best.tok;
+      states[o] = best.next;
+      scores[o] = best.val;
+    }
+    s = best.next;
+    if (COMPARE && stored == s) return;
+    rp += frame_stride;
+    o += B;
   }
-  return s;
+}
+
+// MODE 0: V == 1024, 1: V < 1024, 2: V > 1024 (multi-chunk).
+template <bool COMPARE, int MODE>
+__device__ __forceinline__ void run_frames(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
+                                           int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s,
+                                           int32_t* __restrict__ tokens, int32_t* __restrict__ states,
+                                           float* __restrict__ scores, float* row, unsigned* tag, unsigned& stamp,
+                                           int lane) {
+  if constexpr (MODE == 0)
+    run_frames_1k<COMPARE, true>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, tokens, states, scores, row,
+                                 tag, stamp, lane);
+  else if constexpr (MODE == 1)
+    run_frames_1k<COMPARE, false>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, tokens, states, scores,
+                                  row, tag, stamp, lane);
+  else
+    run_frames_multi<COMPARE>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, tokens, states, scores, row,
+                              tag, stamp, lane);
 }
 
 __device__ __forceinline__ void fill_invalid(int B, int b, int f0, int f1, int32_t* tokens, int32_t* states,
@@ -352,13 +591,14 @@ __device__ __forceinline__ void clear_tags(unsigned* tag, int lane) {
 
 // Pass 1: chain (b, j) decodes segment j of hypothesis b; j = 0 starts from states0[b] (exact),
 // j > 0 from the root (speculative).  One wave per chain.
+template <int MODE>
 __global__ void __launch_bounds__(256) frames_spec_kernel(DeviceTree dt, const float* __restrict__ logp,
                                                           int64_t frame_stride, int64_t row_stride,
                                                           const int32_t* __restrict__ states0, float alpha, int T, int B,
                                                           int seg_len, int nseg, int32_t* __restrict__ tokens,
                                                           int32_t* __restrict__ states, float* __restrict__ scores) {
   extern __shared__ float lds[];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = uniform_i(threadIdx.x >> 6);
   const int chain = blockIdx.x * (blockDim.x >> 6) + wave;
   if (chain >= B * nseg) return;
   const int j = chain / B, b = chain - j * B;
@@ -369,31 +609,32 @@ __global__ void __launch_bounds__(256) frames_spec_kernel(DeviceTree dt, const f
   const int f0 = j * seg_len, f1 = min(T, f0 + seg_len);
   int s = 0;
   if (j == 0) {
-    s = states0[b];
+    s = uniform_i(states0[b]);
     if (!valid_state(t, s)) {
       fill_invalid(B, b, f0, f1, tokens, states, scores, lane);
       return;
     }
   }
   unsigned stamp = 0;
-  run_frames<false>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, tokens, states, scores, row, tag, stamp,
-                    lane, nullptr);
+  run_frames<false, MODE>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, tokens, states, scores, row, tag,
+                          stamp, lane);
 }
 
-// Pass 2: one workgroup per hypothesis, wave j owns segment j.
-//   (a) every wave j > 0 re-runs its segment from the end state pass 1 left in segment j-1 until the
-//       stored trajectory is met;
-//   (b) wave 0 then walks the segments in order: if the end state of segment j-1 is no longer the
-//       state wave j started from, segment j is re-run from the true state the same way.
+// Pass 2: one workgroup per hypothesis; its waves share the segments j = 1 .. nseg-1.
+//   (a) segment j is re-run from the end state pass 1 left in segment j-1 until the stored
+//       trajectory is met;
+//   (b) wave 0 then compares, for all segments at once, the end state of segment j-1 with the
+//       state segment j was re-run from, and repairs mismatches in order the same way.
+template <int MODE>
 __global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, const float* __restrict__ logp,
                                                           int64_t frame_stride, int64_t row_stride, float alpha, int T,
                                                           int B, int seg_len, int nseg, int32_t* __restrict__ tokens,
                                                           int32_t* __restrict__ states, float* __restrict__ scores) {
   extern __shared__ float lds[];
-  __shared__ int assumed[16];
-  const int lane = threadIdx.x & 63, j = threadIdx.x >> 6;
+  __shared__ int assumed[64];
+  const int lane = threadIdx.x & 63, wave = uniform_i(threadIdx.x >> 6), nwaves = blockDim.x >> 6;
   const int b = blockIdx.x;
-  float* row = lds + j * 2 * kChunk;
+  float* row = lds + wave * 2 * kChunk;
   unsigned* tag = reinterpret_cast<unsigned*>(row + kChunk);
   clear_tags(tag, lane);
   const TreeView t = make_view(dt);
@@ -404,55 +645,72 @@ __global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, const f
       fill_invalid(B, b, f0, f1, tokens, states, scores, lane);
       return;
     }
-    run_frames<true>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, tokens, states, scores, row, tag,
-                     stamp, lane, nullptr);
+    run_frames<true, MODE>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, tokens, states, scores, row, tag,
+                           stamp, lane);
   };
-  if (j > 0 && j < nseg) {
-    const int s = states[static_cast<size_t>(j * seg_len - 1) * B + b];
-    if (lane == 0) assumed[j] = s;
-    if (s != 0) rerun(j, s);  // pass 1 assumed the root
+  auto end_state_of = [&](int seg) {  // state after the last frame of segment `seg`
+    const int32_t* p = states + static_cast<size_t>((seg + 1) * seg_len - 1) * B + b;
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  };
+  for (int seg = 1 + wave; seg < nseg; seg += nwaves) {
+    const int s = uniform_i(end_state_of(seg - 1));
+    if (lane == 0) assumed[seg] = s;
+    if (s != 0) rerun(seg, s);  // pass 1 assumed the root
   }
   __threadfence_block();
   __syncthreads();
-  if (j == 0) {
-    for (int seg = 1; seg < nseg; ++seg) {
-      const int32_t* p = states + static_cast<size_t>(seg * seg_len - 1) * B + b;
-      const int true_start = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (true_start != assumed[seg]) rerun(seg, true_start);
+  if (wave == 0) {
+    u64 done = 1;  // segment 0 is exact
+    for (;;) {
+      const bool check = lane >= 1 && lane < nseg;
+      const int have = check ? end_state_of(lane - 1) : 0;
+      const int want = check ? assumed[lane] : 0;
+      const u64 bad = __ballot(check && have != want) & ~done;
+      if (bad == 0) break;
+      const int seg = first_lane(bad);
+      const int s = __builtin_amdgcn_readlane(have, seg);
+      if (lane == 0) assumed[seg] = s;
+      rerun(seg, s);
+      done |= (2ull << seg) - 1;  // segments up to `seg` are final now
     }
   }
 }
 
 // Single step: one wave per hypothesis, no speculation.
+template <int MODE>
 __global__ void __launch_bounds__(256) step_wave_kernel(DeviceTree dt, const float* __restrict__ logp, int64_t row_stride,
                                                         const int32_t* __restrict__ states_in, float alpha, int B,
                                                         int32_t* __restrict__ tokens, int32_t* __restrict__ states_out,
                                                         float* __restrict__ scores) {
   extern __shared__ float lds[];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = uniform_i(threadIdx.x >> 6);
   const int b = blockIdx.x * (blockDim.x >> 6) + wave;
   if (b >= B) return;
   float* row = lds + wave * 2 * kChunk;
   unsigned* tag = reinterpret_cast<unsigned*>(row + kChunk);
   clear_tags(tag, lane);
   const TreeView t = make_view(dt);
-  const int s = states_in[b];
+  const int s = uniform_i(states_in[b]);
   if (!valid_state(t, s)) {
     fill_invalid(B, b, 0, 1, tokens, states_out, scores, lane);
     return;
   }
   unsigned stamp = 0;
-  run_frames<false>(t, logp, 0, row_stride, alpha, B, b, 0, 1, s, tokens, states_out, scores, row, tag, stamp, lane,
-                    nullptr);
+  run_frames<false, MODE>(t, logp, 0, row_stride, alpha, B, b, 0, 1, s, tokens, states_out, scores, row, tag, stamp,
+                          lane);
 }
 
+inline int mode_of(int V) { return V == kChunk ? 0 : (V < kChunk ? 1 : 2); }
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int g_fix_waves = 8;  // waves per fix-up workgroup the device's LDS allows (8 KiB each), set once
 
 }  // namespace
 
 bool wave_path_ok(const DeviceTree& t, const float* d_logp, int64_t frame_stride, int64_t row_stride) {
-  return t.p_root != nullptr && t.vocab_size % 4 == 0 && row_stride % 4 == 0 && frame_stride % 4 == 0 &&
-         aligned16(d_logp) && aligned16(t.root_score);
+  return t.p_root != nullptr && t.root_rec != nullptr && t.vocab_size % 4 == 0 && row_stride % 4 == 0 &&
+         frame_stride % 4 == 0 && aligned16(d_logp) && aligned16(t.root_score);
 }
 
 int launch_step_wave(const DeviceTree& t, const float* d_logp, int64_t row_stride, const int32_t* d_states_in,
@@ -461,18 +719,26 @@ int launch_step_wave(const DeviceTree& t, const float* d_logp, int64_t row_strid
   const int waves = B >= 1024 ? 4 : 1;  // few rows: spread them over as many CUs as possible
   const dim3 grid(static_cast<unsigned>((B + waves - 1) / waves)), block(static_cast<unsigned>(64 * waves));
   const size_t lds = static_cast<size_t>(waves) * 2 * kChunk * sizeof(float);
-  hipLaunchKernelGGL(step_wave_kernel, grid, block, lds, stream, t, d_logp, row_stride, d_states_in, alpha, B, d_tokens,
-                     d_states_out, d_scores);
+#define PB_LAUNCH(MODE)                                                                                         \
+  hipLaunchKernelGGL(step_wave_kernel<MODE>, grid, block, lds, stream, t, d_logp, row_stride, d_states_in, alpha, B, \
+                     d_tokens, d_states_out, d_scores)
+  switch (mode_of(t.vocab_size)) {
+    case 0: PB_LAUNCH(0); break;
+    case 1: PB_LAUNCH(1); break;
+    default: PB_LAUNCH(2); break;
+  }
+#undef PB_LAUNCH
   return hipGetLastError() == hipSuccess ? PB_OK : PB_EHIP;
 }
 
 int launch_frames_wave(const DeviceTree& t, const float* d_logp, int64_t frame_stride, int64_t row_stride,
                        const int32_t* d_states0, float alpha, int32_t T, int32_t B, int32_t* d_tokens,
                        int32_t* d_states, float* d_scores, hipStream_t stream) {
-  // Segments: enough concurrent chains to cover the memory latency, at most 16 per hypothesis
-  // (one wave each in the fix-up workgroup), at least kMinSegLen frames long.
+  // Segments: enough concurrent chains to cover the memory latency, at most kMaxSegments per
+  // hypothesis, at least kMinSegLen frames long.
   int nseg = (kTargetChains + B - 1) / B;
-  nseg = nseg < 1 ? 1 : (nseg > 16 ? 16 : nseg);
+  if (const char* e = getenv("PB_NSEG")) nseg = atoi(e);  // TUNING-ONLY
+  nseg = nseg < 1 ? 1 : (nseg > kMaxSegments ? kMaxSegments : nseg);
   int seg_len = (T + nseg - 1) / nseg;
   if (seg_len < kMinSegLen) seg_len = kMinSegLen;
   nseg = (T + seg_len - 1) / seg_len;
@@ -481,23 +747,54 @@ int launch_frames_wave(const DeviceTree& t, const float* d_logp, int64_t frame_s
   const int64_t blocks = (chains + waves - 1) / waves;
   if (blocks > INT32_MAX) return PB_EUNSUPPORTED;
   const size_t lds = static_cast<size_t>(waves) * 2 * kChunk * sizeof(float);
-  hipLaunchKernelGGL(frames_spec_kernel, dim3(static_cast<unsigned>(blocks)), dim3(64 * waves), lds, stream, t, d_logp,
-                     frame_stride, row_stride, d_states0, alpha, T, B, seg_len, nseg, d_tokens, d_states, d_scores);
+#define PB_LAUNCH(MODE)                                                                                              \
+  hipLaunchKernelGGL(frames_spec_kernel<MODE>, dim3(static_cast<unsigned>(blocks)), dim3(64 * waves), lds, stream, t, \
+                     d_logp, frame_stride, row_stride, d_states0, alpha, T, B, seg_len, nseg, d_tokens, d_states,      \
+                     d_scores)
+  const int mode = mode_of(t.vocab_size);
+  switch (mode) {
+    case 0: PB_LAUNCH(0); break;
+    case 1: PB_LAUNCH(1); break;
+    default: PB_LAUNCH(2); break;
+  }
+#undef PB_LAUNCH
   if (hipGetLastError() != hipSuccess) return PB_EHIP;
   if (nseg > 1) {
-    const size_t lds2 = static_cast<size_t>(nseg) * 2 * kChunk * sizeof(float);
-    hipLaunchKernelGGL(frames_fix_kernel, dim3(static_cast<unsigned>(B)), dim3(64 * nseg), lds2, stream, t, d_logp,
-                       frame_stride, row_stride, alpha, T, B, seg_len, nseg, d_tokens, d_states, d_scores);
+    int fw = nseg - 1 < g_fix_waves ? nseg - 1 : g_fix_waves;
+    const size_t lds2 = static_cast<size_t>(fw) * 2 * kChunk * sizeof(float);
+#define PB_LAUNCH(MODE)                                                                                          \
+  hipLaunchKernelGGL(frames_fix_kernel<MODE>, dim3(static_cast<unsigned>(B)), dim3(64 * fw), lds2, stream, t, d_logp, \
+                     frame_stride, row_stride, alpha, T, B, seg_len, nseg, d_tokens, d_states, d_scores)
+    switch (mode) {
+      case 0: PB_LAUNCH(0); break;
+      case 1: PB_LAUNCH(1); break;
+      default: PB_LAUNCH(2); break;
+    }
+#undef PB_LAUNCH
     if (hipGetLastError() != hipSuccess) return PB_EHIP;
   }
   return PB_OK;
 }
 
 int prepare_wave_kernels() {
-  // the fix-up workgroup may need more than the default 64 KiB of dynamic LDS (16 waves x 8 KiB)
-  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(frames_fix_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 16 * 2 * kChunk * 4);
-  return e == hipSuccess ? PB_OK : PB_EHIP;
+  // The fix-up workgroup uses 8 KiB of dynamic LDS per wave; more than 8 waves need the limit raised.
+  int dev = 0, max_lds = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return PB_EHIP;
+  if (hipDeviceGetAttribute(&max_lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return PB_EHIP;
+  int waves = (max_lds - 1024) / (2 * kChunk * 4);
+  waves = waves > 16 ? 16 : (waves < 1 ? 1 : waves);
+  if (waves > 8) {
+    const int bytes = waves * 2 * kChunk * 4;
+    const hipFuncAttribute attr = hipFuncAttributeMaxDynamicSharedMemorySize;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(frames_fix_kernel<0>), attr, bytes) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void*>(frames_fix_kernel<1>), attr, bytes) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void*>(frames_fix_kernel<2>), attr, bytes) != hipSuccess) {
+      (void)hipGetLastError();
+      waves = 8;
+    }
+  }
+  g_fix_waves = waves;
+  return PB_OK;
 }
 
 }  // namespace pb

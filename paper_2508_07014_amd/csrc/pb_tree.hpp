@@ -21,6 +21,19 @@ struct alignas(8) ArcRec {
   float score;
 };
 
+// One 32-byte record per token: where the root row sends the token (a depth-1 state, or the root
+// itself for the c_unk self-loop) together with that state's record, so that following a root arc
+// costs one load.
+struct alignas(32) RootRec {
+  int32_t next;       // target state
+  int32_t arc_begin;  // StateRec of the target ...
+  int32_t arc_count;
+  int32_t fail;
+  float backoff;
+  float p_root;       // ... and its total backoff down to the root
+  int32_t pad0, pad1;
+};
+
 // Device mirror (one allocation, sub-arrays aligned to 256 bytes).
 struct DeviceTree {
   const StateRec* state = nullptr;  // [N]
@@ -28,6 +41,7 @@ struct DeviceTree {
   const float* root_score = nullptr;  // [V]
   const int32_t* root_next = nullptr;  // [V]
   const float* p_root = nullptr;       // [N] backoff accumulated from the state down to the root (fp32, chain order)
+  const RootRec* root_rec = nullptr;   // [V]
   int32_t num_states = 0;
   int32_t vocab_size = 0;
   int32_t blank_id = -1;
@@ -38,6 +52,7 @@ struct HostTree {
   int32_t max_depth = 0, max_fail_chain = 0, root_degree = 0;
   std::vector<StateRec> state;
   std::vector<ArcRec> arc;
+  std::vector<RootRec> root_rec;
   std::vector<int32_t> arc_begin, arc_count, fail, depth, parent, arc_token, root_next;
   std::vector<float> backoff, arc_score, root_score, p_root;
   std::vector<uint8_t> is_final;
