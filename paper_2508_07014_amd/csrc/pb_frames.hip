@@ -373,27 +373,24 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
                                               int lane) {
   const int V = t.V;
   const float* rp = logp + static_cast<size_t>(b) * row_stride + static_cast<size_t>(f0) * frame_stride;
-  float buf[3][16], rw[16], c[16];
-  if (f0 < f1) load16<FULL>(rp, 0, V, lane, -INFINITY, buf[0]);
-  if (f0 + 1 < f1) load16<FULL>(rp + frame_stride, 0, V, lane, -INFINITY, buf[1]);
+  float buf[2][16], rw[16], c[16];
   load16<FULL>(t.root_score, 0, V, lane, 0.0f, rw);
+  if (f0 < f1) load16<FULL>(rp, 0, V, lane, -INFINITY, buf[0]);
   Cursor cur = cursor_at(t, s);
   float c_p = cur.p_root;
   make_base_boost(0, lane, t.blank, c_p, alpha, rw, c);
   size_t o = static_cast<size_t>(f0) * B + b;
   bool stop = false;
-  for (int fb = f0; fb < f1 && !stop; fb += 3) {
+  for (int fb = f0; fb < f1 && !stop; fb += 2) {
 #pragma unroll
-    for (int u = 0; u < 3; ++u) {
+    for (int u = 0; u < 2; ++u) {
       const int f = fb + u;
       if (f < f1 && !stop) {
+        // the next row is requested before this one is looked at
+        if (f + 1 < f1) load16<FULL>(rp + frame_stride, 0, V, lane, -INFINITY, buf[(u + 1) % 2]);
         float val;
         int tok;
-        frame_1k(t, cur, buf[u], c, c_p, rw, alpha, row, tag, stamp, lane,
-                 [&]() {
-                   if (f + 2 < f1) load16<FULL>(rp + 2 * frame_stride, 0, V, lane, -INFINITY, buf[(u + 2) % 3]);
-                 },
-                 val, tok);
+        frame_1k(t, cur, buf[u], c, c_p, rw, alpha, row, tag, stamp, lane, []() {}, val, tok);
         int stored = 0;
         if (COMPARE) stored = uniform_i(__hip_atomic_load(states + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
         if (lane == 0) {
