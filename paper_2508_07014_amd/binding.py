@@ -61,6 +61,10 @@ def load():
         return _lib
     if not os.path.exists(_build.LIB):
         _build.build(force=True)
+    try:  # PyTorch ships its own HIP runtime: let it load first so the process ends up with one copy
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(_build.LIB)
     vp, i32p, i64p, f32p = C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_float)
     lib.pb_build.restype = C.c_int

@@ -32,7 +32,6 @@
 #include <climits>
 #include <cmath>
 #include <cstdint>
-#include <cstdlib>
 
 #include "pb_kernels.hpp"
 
@@ -734,7 +733,6 @@ int launch_frames_wave(const DeviceTree& t, const float* d_logp, int64_t frame_s
   // Segments: enough concurrent chains to cover the memory latency, at most kMaxSegments per
   // hypothesis, at least kMinSegLen frames long.
   int nseg = (kTargetChains + B - 1) / B;
-  if (const char* e = getenv("PB_NSEG")) nseg = atoi(e);  // TUNING-ONLY
   nseg = nseg < 1 ? 1 : (nseg > kMaxSegments ? kMaxSegments : nseg);
   int seg_len = (T + nseg - 1) / nseg;
   if (seg_len < kMinSegLen) seg_len = kMinSegLen;

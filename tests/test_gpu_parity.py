@@ -322,3 +322,108 @@ def test_results_are_deterministic_run_to_run():
     b = gpu_fuse_frames(tr, logp, s0, cfg.alpha)
     for x, y in zip(a, b):
         assert np.array_equal(x, y)
+
+
+# ------------------------------------------------------------------- rare paths of the wave kernels
+
+def _adversarial_tree(seed, V):
+    """Tiny vocabulary, mixed-sign phrase weights and a large unknown-token score: overriding arcs often
+    score *below* the root row they shadow, so the base winner is regularly an overridden token."""
+    rng = np.random.default_rng(seed)
+    toks, offs, _ = W.tiny_case(12000 + seed, vocab_size=min(V, 7), blank_id=0, max_phrases=12, max_len=6)
+    wts = rng.choice(np.array([-2.0, -1.0, -0.5, 0.25, 1.0, 2.0], np.float32), size=len(offs) - 1)
+    mode = W_LOGDEPTH if seed % 2 else W_UNIFORM
+    kw = dict(weights=wts, weight_mode=mode, beta=float(rng.choice([-1.0, 0.5, 2.0])),
+              unk_score=float(rng.choice([0.0, 1.5, -0.75])), final_zero_backoff=bool(seed % 3))
+    return build_both(toks, offs, V, 0, **kw)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_fuse_overridden_base_winner_and_shadowed_arcs(seed):
+    V = [8, 12, 64, 1024][seed % 4]
+    ot, tr = _adversarial_tree(seed, V)
+    rng = np.random.default_rng(seed)
+    B, T = 24, 40
+    # flat logits: the boost decides; the few live tokens are where the phrases are
+    raw = rng.standard_normal((T, B, V)) * 0.3
+    raw[:, :, 7:] -= 6.0
+    logp = W.log_softmax_rows(raw)
+    alpha = float(rng.choice([0.5, 1.0, 2.0]))
+    # every state as a start state, step by step
+    states = np.arange(ot.num_states, dtype=np.int32)
+    lp = np.repeat(logp[0, :1], len(states), axis=0)
+    want = ot.fuse_step(lp, states, alpha)
+    tk, st, sc = gpu_fuse_step(tr, dev(lp), dev(states), alpha)
+    torch.cuda.synchronize()
+    assert np.array_equal(tk.cpu().numpy(), want[0]) and np.array_equal(st.cpu().numpy(), want[1])
+    assert_scores(sc.cpu().numpy(), want[2])
+    # and chained over frames, from random start states
+    s0 = rng.integers(0, ot.num_states, B).astype(np.int32)
+    wantf = ot.fuse_frames(logp, s0, alpha)
+    gotf = gpu_fuse_frames(tr, dev(logp), dev(s0), alpha)
+    assert np.array_equal(gotf[0], wantf[0]) and np.array_equal(gotf[1], wantf[1])
+    assert_scores(gotf[2], wantf[2])
+
+
+@pytest.mark.parametrize("idx,T,B", [(2, 200, 4), (3, 260, 8), (1, 97, 3), (5, 64, 8)])
+def test_fuse_frames_long_phrases_across_segment_boundaries(idx, T, B):
+    """Few hypotheses: many short speculative segments.  Almost every frame follows a listed phrase, so
+    a segment started from the root keeps disagreeing with the true state for longer than a segment
+    lasts and the ordered repair pass has to run."""
+    cfg, toks, offs, ot, tr = config_trees(idx)
+    logp = W.make_logp(cfg, steps=T, batch=B, planting=W.Planting(toks, offs, cover=0.92, truncate=0.1, bump=6.0 * cfg.sigma))
+    want = ot.fuse_frames(logp, np.zeros(B, np.int32), cfg.alpha)
+    got = gpu_fuse_frames(tr, dev(logp), dev(np.zeros(B, np.int32)), cfg.alpha)
+    assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1])
+    assert_scores(got[2], want[2])
+    depth = np.array([ot.node(int(s))["depth"] for s in want[1][:, 0]])
+    assert depth.max() >= min(6, ot.max_depth) and (depth >= 2).mean() > 0.3
+
+
+def test_fuse_frames_invalid_start_state_marks_whole_hypothesis():
+    cfg, toks, offs, ot, tr = config_trees(2)
+    T, B = 120, 6
+    logp = W.make_logp(cfg, steps=T, batch=B)
+    s0 = np.zeros(B, np.int32)
+    s0[2] = ot.num_states + 7
+    s0[4] = -1
+    got = gpu_fuse_frames(tr, dev(logp), dev(s0), cfg.alpha)
+    ok = [0, 1, 3, 5]
+    want = ot.fuse_frames(logp[:, ok], s0[ok], cfg.alpha)
+    assert np.array_equal(got[0][:, ok], want[0]) and np.array_equal(got[1][:, ok], want[1])
+    for b in (2, 4):
+        assert np.all(got[0][:, b] == -1) and np.all(got[1][:, b] == -1) and np.all(np.isnan(got[2][:, b]))
+
+
+def test_fuse_frames_strided_rows_and_frames():
+    cfg, toks, offs, ot, tr = config_trees(2)
+    T, B, V = 50, 5, cfg.vocab_size
+    logp = W.make_logp(cfg, steps=T, batch=B, planting=W.Planting(toks, offs, cover=0.5))
+    rs, fs = V + 8, B * (V + 8) + 16
+    buf = np.full(T * fs, 50.0, np.float32)
+    for t in range(T):
+        for b in range(B):
+            buf[t * fs + b * rs: t * fs + b * rs + V] = logp[t, b]
+    d_buf = dev(buf)
+    d_tok = torch.zeros((T, B), dtype=torch.int32, device=DEV)
+    d_st = torch.zeros((T, B), dtype=torch.int32, device=DEV)
+    d_sc = torch.zeros((T, B), dtype=torch.float32, device=DEV)
+    pb.pb_fuse_frames(tr, d_buf, fs, rs, dev(np.zeros(B, np.int32)), cfg.alpha, T, B, d_tok, d_st, d_sc, stream_ptr())
+    torch.cuda.synchronize()
+    want = ot.fuse_frames(logp, np.zeros(B, np.int32), cfg.alpha)
+    assert np.array_equal(d_tok.cpu().numpy(), want[0]) and np.array_equal(d_st.cpu().numpy(), want[1])
+
+
+def test_fuse_exact_ties_between_arcs_in_different_lanes():
+    """Flat log-probs: all children of a state tie exactly, and so do all root arcs; lowest token wins."""
+    cfg, toks, offs, ot, tr = config_trees(2)
+    V = cfg.vocab_size
+    deg = [(ot.node(s)["depth"], s) for s in range(1, 300)]
+    states = np.array([0] + [s for d, s in deg if d == 1][:40] + [s for d, s in deg if d == 2][:20], np.int32)
+    for const, alpha in [(-4.0, 0.5), (-np.inf, 0.5), (-4.0, 0.0)]:
+        logp = np.full((len(states), V), const, np.float32)
+        want = ot.fuse_step(logp, states, alpha)
+        tk, st, sc = gpu_fuse_step(tr, dev(logp), dev(states), alpha)
+        torch.cuda.synchronize()
+        assert np.array_equal(tk.cpu().numpy(), want[0]) and np.array_equal(st.cpu().numpy(), want[1])
+        assert np.array_equal(sc.cpu().numpy(), want[2])
