@@ -4,7 +4,7 @@
 //
 //  * Row streaming.  A row is consumed in chunks of 1024 tokens; lane l owns tokens
 //    256*i + 4*l + {0..3}, i = 0..3 of a chunk, so each of the four 16-byte loads of a lane is part
-//    of one contiguous 1 KiB wave access.  Chunks are prefetched two ahead into registers.
+//    of one contiguous 1 KiB wave access.  The next row is requested before the current one is used.
 //  * Base candidates.  For every token that no chain state overrides the boost is
 //    p_root + root_score[v] (all backoffs down to the root, then the root arc or the c_unk
 //    self-loop).  alpha * that is cached per lane while p_root does not change, so the common
@@ -361,12 +361,24 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
   out_tok = uniform_i(out_tok);
 }
 
-// Decodes frames [f0, f1) of hypothesis b (V <= 1024) starting in valid state s.  With COMPARE set,
+__device__ __forceinline__ void fill_invalid(int B, int b, int f0, int f1, int32_t* tokens, int32_t* states,
+                                             float* scores, int lane) {
+  for (int f = f0 + lane; f < f1; f += 64) {
+    const size_t o = static_cast<size_t>(f) * B + b;
+    tokens[o] = -1;
+    states[o] = -1;
+    scores[o] = NAN;
+  }
+}
+
+// Decodes frames [f0, f1) of hypothesis b (V <= 1024) starting in state s_in (a value that may still be
+// in flight from a load: it is first looked at after the row loads have been issued; an invalid
+// state marks the frames).  With COMPARE set,
 // stops after the first frame whose out-state equals the one already stored in `states` (the
 // stored trajectory is then valid from there on).
 template <bool COMPARE, bool FULL>
 __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
-                                              int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s,
+                                              int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s_in,
                                               int32_t* __restrict__ tokens, int32_t* __restrict__ states,
                                               float* __restrict__ scores, float* row, unsigned* tag, unsigned& stamp,
                                               int lane) {
@@ -375,6 +387,11 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
   float buf[2][16], rw[16], c[16];
   load16<FULL>(t.root_score, 0, V, lane, 0.0f, rw);
   if (f0 < f1) load16<FULL>(rp, 0, V, lane, -INFINITY, buf[0]);
+  const int s = uniform_i(s_in);
+  if (!valid_state(t, s)) {
+    fill_invalid(B, b, f0, f1, tokens, states, scores, lane);
+    return;
+  }
   Cursor cur = cursor_at(t, s);
   float c_p = cur.p_root;
   make_base_boost(0, lane, t.blank, c_p, alpha, rw, c);
@@ -509,10 +526,15 @@ __device__ __forceinline__ Win decide_chunk(const TreeView& t, int s, int cb, co
 
 template <bool COMPARE>
 __device__ __forceinline__ void run_frames_multi(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
-                                                 int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s,
+                                                 int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s_in,
                                                  int32_t* __restrict__ tokens, int32_t* __restrict__ states,
                                                  float* __restrict__ scores, float* row, unsigned* tag, unsigned& stamp,
                                                  int lane) {
+  int s = uniform_i(s_in);
+  if (!valid_state(t, s)) {
+    fill_invalid(B, b, f0, f1, tokens, states, scores, lane);
+    return;
+  }
   const int V = t.V;
   const int nch = (V + kChunk - 1) / kChunk;
   const float* rp = logp + static_cast<size_t>(b) * row_stride + static_cast<size_t>(f0) * frame_stride;
@@ -570,16 +592,6 @@ __device__ __forceinline__ void run_frames(const TreeView& t, const float* __res
                               tag, stamp, lane);
 }
 
-__device__ __forceinline__ void fill_invalid(int B, int b, int f0, int f1, int32_t* tokens, int32_t* states,
-                                             float* scores, int lane) {
-  for (int f = f0 + lane; f < f1; f += 64) {
-    const size_t o = static_cast<size_t>(f) * B + b;
-    tokens[o] = -1;
-    states[o] = -1;
-    scores[o] = NAN;
-  }
-}
-
 __device__ __forceinline__ void clear_tags(unsigned* tag, int lane) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(tag + 256 * i + 4 * lane) = make_uint4(0u, 0u, 0u, 0u);
@@ -604,13 +616,7 @@ __global__ void __launch_bounds__(256) frames_spec_kernel(DeviceTree dt, const f
   const TreeView t = make_view(dt);
   const int f0 = j * seg_len, f1 = min(T, f0 + seg_len);
   int s = 0;
-  if (j == 0) {
-    s = uniform_i(states0[b]);
-    if (!valid_state(t, s)) {
-      fill_invalid(B, b, f0, f1, tokens, states, scores, lane);
-      return;
-    }
-  }
+  if (j == 0) s = states0[b];
   unsigned stamp = 0;
   run_frames<false, MODE>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, tokens, states, scores, row, tag,
                           stamp, lane);
@@ -637,10 +643,6 @@ __global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, const f
   unsigned stamp = 0;
   auto rerun = [&](int seg, int s) {
     const int f0 = seg * seg_len, f1 = min(T, f0 + seg_len);
-    if (!valid_state(t, s)) {
-      fill_invalid(B, b, f0, f1, tokens, states, scores, lane);
-      return;
-    }
     run_frames<true, MODE>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, tokens, states, scores, row, tag,
                            stamp, lane);
   };
@@ -649,9 +651,9 @@ __global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, const f
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   };
   for (int seg = 1 + wave; seg < nseg; seg += nwaves) {
-    const int s = uniform_i(end_state_of(seg - 1));
+    const int s = end_state_of(seg - 1);  // consumed inside rerun, after its row loads are on their way
     if (lane == 0) assumed[seg] = s;
-    if (s != 0) rerun(seg, s);  // pass 1 assumed the root
+    rerun(seg, s);  // pass 1 assumed the root: a segment whose neighbour ended there meets at once
   }
   __threadfence_block();
   __syncthreads();
@@ -686,11 +688,7 @@ __global__ void __launch_bounds__(256) step_wave_kernel(DeviceTree dt, const flo
   unsigned* tag = reinterpret_cast<unsigned*>(row + kChunk);
   clear_tags(tag, lane);
   const TreeView t = make_view(dt);
-  const int s = uniform_i(states_in[b]);
-  if (!valid_state(t, s)) {
-    fill_invalid(B, b, 0, 1, tokens, states_out, scores, lane);
-    return;
-  }
+  const int s = states_in[b];
   unsigned stamp = 0;
   run_frames<false, MODE>(t, logp, 0, row_stride, alpha, B, b, 0, 1, s, tokens, states_out, scores, row, tag, stamp,
                           lane);
