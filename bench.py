@@ -150,10 +150,74 @@ def main() -> int:
                                f"{cpu_s:.2f} s wall"}
         out["parity"] = bool(np.array_equal(d_tok.cpu().numpy(), want[0]) and
                              np.array_equal(d_st.cpu().numpy(), want[1]))
+        # the same oracle on one thread, on the first 100 frames
+        from oracle import set_oracle_threads
+        nthreads = oracle_threads()
+        set_oracle_threads(1)
+        c0 = time.perf_counter()
+        ot.fuse_frames(logp[:100], np.zeros(B, np.int32), cfg.alpha)
+        out["cpu_baseline"]["one_thread_value"] = B * 100 / (time.perf_counter() - c0)
+        set_oracle_threads(nthreads)
 
     # ---- side measurements ---------------------------------------------------------------------------
     if not args.no_extra:
         extra = {}
+        # what a plain device copy reaches on this machine (read + write bytes), and the headline against it
+        src = torch.ones(64 << 20, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        ms = _events(torch, lambda: dst.copy_(src), 10)
+        copy_gbs = 2 * src.numel() * 4 / (ms * 1e-3) / 1e9
+        del src, dst
+        extra["copy_256MiB"] = {"GBps": copy_gbs, "frac_hbm": copy_gbs / HBM_PEAK_GBS,
+                                "headline_frac_of_copy": achieved / copy_gbs}
+        # latency of one dependent load i = table[i] through a random cyclic permutation.  Every timed
+        # launch starts at a fresh place of the cycle, so its lines are touched for the first time since
+        # the preparation step: "L2" = small table read beforehand, "MALL" = 64 MiB table read beforehand,
+        # "HBM" = 1 GiB table after 512 MiB of unrelated traffic.
+        chase = {}
+        d_one = torch.zeros(1, dtype=torch.int32, device=dev)
+        hops = 20000
+        for label, n in (("L2_256KiB_table", 1 << 16), ("MALL_64MiB_table", 1 << 24), ("HBM_1GiB_table", 1 << 28)):
+            rng = np.random.Generator(np.random.PCG64(n))
+            order = rng.permutation(n).astype(np.int32)
+            table = np.empty(n, np.int32)
+            table[order] = np.roll(order, -1)
+            d_table = torch.from_numpy(table).to(dev)
+            pb.pb_diag_chase(d_table, n, 0, 10, d_one, stream)
+            if n <= (1 << 24):
+                d_table.sum()
+            else:
+                junk = torch.ones(64 << 20, dtype=torch.float32, device=dev)
+                junk2 = junk.clone()
+                del junk, junk2
+            torch.cuda.synchronize()
+            starts = [int(order[(k + 1) * (n // 4)]) for k in range(3)]
+            it = iter(starts)
+            ms = _events(torch, lambda: pb.pb_diag_chase(d_table, n, next(it), hops, d_one, stream), 3)
+            chase[label] = {"ns_per_hop": ms * 1e6 / hops}
+            del d_table, table, order
+        extra["dependent_load_latency"] = chase
+        # structured variants of config 3 through the same entry point (parity checked)
+        variants = {"planted_20pct": dict(planting=W.Planting(toks, offs)),
+                    "blank_dominated_75pct": dict(blank_bias=8.0, blank_frac=0.75)}
+        results = {}
+        for name, kw in variants.items():
+            lp = W.make_logp(cfg, **kw)
+            d_lp = torch.from_numpy(lp).to(dev)
+            fn = lambda: pb.pb_fuse_frames(tree, d_lp, B * V, V, d_s0, cfg.alpha, T, B, d_tok, d_st, d_sc, stream)
+            fn()
+            ms = _events(torch, fn, 5)
+            rec = {"ms": ms, "hyp_frames_per_s": B * T / (ms * 1e-3), "GBps": bytes_per_launch / (ms * 1e-3) / 1e9,
+                   "frac_hbm": bytes_per_launch / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+            if not args.no_cpu:
+                w = ot.fuse_frames(lp, np.zeros(B, np.int32), cfg.alpha)
+                rec["parity"] = bool(np.array_equal(d_tok.cpu().numpy(), w[0]) and
+                                     np.array_equal(d_st.cpu().numpy(), w[1]))
+                rec["mean_state_depth_gt1_frac"] = float(np.mean(w[1] > info["root_degree"]))
+            results[name] = rec
+            del d_lp, lp
+        extra["config3_variants"] = results
         # one launch per frame (the RNN-T / AED shaped loop): states ping through a [T,B] buffer
         frames = min(T, 200)
 
@@ -207,6 +271,23 @@ def main() -> int:
             sweep[f"B{Bs}"] = {"us": ms * 1e3, "scores_per_s": Bs * cfg5.vocab_size / (ms * 1e-3),
                                "GBps": byts / (ms * 1e-3) / 1e9, "frac_hbm": byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
         extra["pb_score_v8192_uniform_states"] = sweep
+        # the same call on states of a greedy trajectory (mostly the root and depth 1)
+        lp5 = torch.from_numpy(W.make_logp(cfg5, steps=8, batch=1024)).to(dev)
+        tr_tok = torch.empty((8, 1024), dtype=torch.int32, device=dev)
+        tr_st = torch.empty((8, 1024), dtype=torch.int32, device=dev)
+        tr_sc = torch.empty((8, 1024), dtype=torch.float32, device=dev)
+        pb.pb_fuse_frames(tree5, lp5, 1024 * cfg5.vocab_size, cfg5.vocab_size,
+                          torch.zeros(1024, dtype=torch.int32, device=dev), cfg5.alpha, 8, 1024, tr_tok, tr_st, tr_sc,
+                          stream)
+        st = tr_st[7].contiguous()
+        fn = lambda: pb.pb_score(tree5, st, 1024, sc, nx, stream)
+        fn()
+        ms = _events(torch, fn, 20)
+        byts = 1024 * cfg5.vocab_size * 8 + 4 * 1024
+        extra["pb_score_v8192_trajectory_states"] = {"B1024": {
+            "us": ms * 1e3, "scores_per_s": 1024 * cfg5.vocab_size / (ms * 1e-3), "GBps": byts / (ms * 1e-3) / 1e9,
+            "frac_hbm": byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}}
+        del lp5
         # beam step: config 4 shape (32 utterances x 4 beams, 5K phrases)
         cfg4 = W.CONFIGS[4]
         t4, o4 = W.make_phrases(cfg4)

@@ -166,6 +166,17 @@ int pb_fuse_step_beam(const pb_tree* tree, const float* d_logp, int64_t row_stri
                       const int32_t* d_states_in, float alpha, int32_t U, int32_t K, int32_t* d_tokens,
                       int32_t* d_parents, int32_t* d_states_out, float* d_scores_out, void* hip_stream);
 
+/*
+ * pb_diag_chase -- measurement aid, not part of the method: one GPU lane performs `hops` dependent
+ * loads i = d_table[i] starting at i = start and writes the last index to *d_out.  Timed by the
+ * caller (events on the stream), it gives the latency of one dependent access for a table of n
+ * entries -- the floor under every per-step call, whose state -> arcs -> next-state recurrence is
+ * such a chain.  d_table int32[n], every entry in [0, n) (the caller's responsibility: entries are
+ * not checked on the device); asynchronous on `hip_stream`.  PB_EINVAL for null pointers, n <= 0 or
+ * n >= 2^31, start outside [0, n), hops < 0.
+ */
+int pb_diag_chase(const int32_t* d_table, int64_t n, int32_t start, int32_t hops, int32_t* d_out, void* hip_stream);
+
 const char* pb_strerror(int code);
 
 #ifdef __cplusplus

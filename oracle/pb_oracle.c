@@ -371,6 +371,15 @@ int32_t orc_fuse_step_beam(const orc_tree *t, const float *logp, int64_t row_str
   return fail_alloc ? ORC_ENOMEM : ORC_OK;
 }
 
+/* Timing aid: number of threads the OpenMP loops above may use (no effect without OpenMP). */
+void orc_set_threads(int32_t n) {
+#ifdef _OPENMP
+  if (n > 0) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
+}
+
 int32_t orc_threads(void) {
 #ifdef _OPENMP
   return omp_get_max_threads();

@@ -71,6 +71,8 @@ def _load():
     lib.orc_fuse_step_beam.restype = C.c_int32
     lib.orc_fuse_step_beam.argtypes = [C.c_void_p, f32p, C.c_int64, f32p, i32p, C.c_float, C.c_int32,
                                        C.c_int32, i32p, i32p, i32p, f32p]
+    lib.orc_set_threads.restype = None
+    lib.orc_set_threads.argtypes = [C.c_int32]
     lib.orc_threads.restype = C.c_int32
     lib.orc_threads.argtypes = []
     _lib = lib
@@ -80,6 +82,11 @@ def _load():
 def oracle_threads() -> int:
     """Threads the oracle's OpenMP loops use (one hypothesis / utterance per iteration)."""
     return int(_load().orc_threads())
+
+
+def set_oracle_threads(n: int) -> None:
+    """Timing aid: thread count of the oracle's OpenMP loops."""
+    _load().orc_set_threads(int(n))
 
 
 def _p(a: Optional[np.ndarray], ct):

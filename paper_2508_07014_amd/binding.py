@@ -17,7 +17,7 @@ PB_OK, PB_EINVAL, PB_ERANGE, PB_ENOMEM, PB_EHIP, PB_EUNSUPPORTED = 0, -1, -2, -3
 PB_W_UNIFORM, PB_W_LOGDEPTH = 0, 1
 
 EXPORTS = ["pb_build", "pb_free", "pb_info", "pb_host_arrays", "pb_state_prefix", "pb_score", "pb_fuse_step",
-           "pb_fuse_frames", "pb_fuse_step_beam", "pb_strerror"]
+           "pb_fuse_frames", "pb_fuse_step_beam", "pb_diag_chase", "pb_strerror"]
 
 
 class PbError(RuntimeError):
@@ -85,6 +85,8 @@ def load():
     lib.pb_fuse_frames.argtypes = [vp, vp, C.c_int64, C.c_int64, vp, C.c_float, C.c_int32, C.c_int32, vp, vp, vp, vp]
     lib.pb_fuse_step_beam.restype = C.c_int
     lib.pb_fuse_step_beam.argtypes = [vp, vp, C.c_int64, vp, vp, C.c_float, C.c_int32, C.c_int32, vp, vp, vp, vp, vp]
+    lib.pb_diag_chase.restype = C.c_int
+    lib.pb_diag_chase.argtypes = [vp, C.c_int64, C.c_int32, C.c_int32, vp, vp]
     lib.pb_strerror.restype = C.c_char_p
     lib.pb_strerror.argtypes = [C.c_int]
     _lib = lib
@@ -199,3 +201,7 @@ def pb_fuse_step_beam(tree: Tree, d_logp, row_stride: int, d_hyp_scores, d_state
     _check(load().pb_fuse_step_beam(tree.handle, _dptr(d_logp), row_stride, _dptr(d_hyp_scores), _dptr(d_states_in),
                                     alpha, U, K, _dptr(d_tokens), _dptr(d_parents), _dptr(d_states_out),
                                     _dptr(d_scores_out), stream or None), "pb_fuse_step_beam")
+
+
+def pb_diag_chase(d_table, n: int, start: int, hops: int, d_out, stream: int = 0):
+    _check(load().pb_diag_chase(_dptr(d_table), n, start, hops, _dptr(d_out), stream or None), "pb_diag_chase")

@@ -2,6 +2,7 @@
 // the compiled tree, and dispatch to the kernel launchers.
 #include <hip/hip_runtime.h>
 
+#include <climits>
 #include <cstring>
 #include <new>
 
@@ -199,6 +200,11 @@ int pb_fuse_step_beam(const pb_tree* tree, const float* d_logp, int64_t row_stri
   if (static_cast<int64_t>(U) * K > INT32_MAX) return PB_EUNSUPPORTED;
   return pb::launch_beam(tree->dev, d_logp, row_stride, d_hyp_scores, d_states_in, alpha, U, K, d_tokens, d_parents,
                          d_states_out, d_scores_out, static_cast<hipStream_t>(hip_stream));
+}
+
+int pb_diag_chase(const int32_t* d_table, int64_t n, int32_t start, int32_t hops, int32_t* d_out, void* hip_stream) {
+  if (!d_table || !d_out || n <= 0 || n > INT32_MAX || start < 0 || start >= n || hops < 0) return PB_EINVAL;
+  return pb::launch_chase(d_table, start, hops, d_out, static_cast<hipStream_t>(hip_stream));
 }
 
 const char* pb_strerror(int code) {

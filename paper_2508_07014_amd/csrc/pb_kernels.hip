@@ -362,6 +362,16 @@ __global__ void __launch_bounds__(1024) beam_kernel(DeviceTree t, const float* _
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Dependent-load latency probe: one lane follows table[i] for `hops` loads.  The decode recurrence
+// (state -> record -> arcs -> next state) is a chain of such loads, so this is the per-hop floor
+// of every single-step call.
+__global__ void chase_kernel(const int32_t* __restrict__ table, int32_t start, int32_t hops, int32_t* __restrict__ out) {
+  int32_t i = start + static_cast<int32_t>(threadIdx.x);  // launched with one thread; keeps the loads on the vector path
+  for (int32_t h = 0; h < hops; ++h) i = table[i];
+  *out = i;
+}
+
 inline int pick_chunk(int V) { return V < kMaxChunk ? ((V + 3) & ~3) : kMaxChunk; }
 
 inline int pick_threads(int V) {
@@ -405,6 +415,11 @@ int launch_fuse(const DeviceTree& t, const float* d_logp, int64_t frame_stride, 
   else
     hipLaunchKernelGGL(fuse_kernel<1>, grid, block, lds, stream, t, d_logp, frame_stride, row_stride, d_states0, alpha,
                        T, B, d_tokens, d_states, d_scores, chunk);
+  return check_launch();
+}
+
+int launch_chase(const int32_t* d_table, int32_t start, int32_t hops, int32_t* d_out, hipStream_t stream) {
+  hipLaunchKernelGGL(chase_kernel, dim3(1), dim3(1), 0, stream, d_table, start, hops, d_out);
   return check_launch();
 }
 

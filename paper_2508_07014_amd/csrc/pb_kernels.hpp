@@ -31,6 +31,9 @@ int launch_frames_wave(const DeviceTree& t, const float* d_logp, int64_t frame_s
                        const int32_t* d_states0, float alpha, int32_t T, int32_t B, int32_t* d_tokens,
                        int32_t* d_states, float* d_scores, hipStream_t stream);
 
+// Latency probe: `hops` dependent loads through d_table (every entry a valid index into it).
+int launch_chase(const int32_t* d_table, int32_t start, int32_t hops, int32_t* d_out, hipStream_t stream);
+
 int launch_beam(const DeviceTree& t, const float* d_logp, int64_t row_stride, const float* d_hyp,
                 const int32_t* d_states_in, float alpha, int32_t U, int32_t K, int32_t* d_tokens, int32_t* d_parents,
                 int32_t* d_states_out, float* d_scores_out, hipStream_t stream);
