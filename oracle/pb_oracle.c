@@ -322,6 +322,81 @@ int32_t orc_fuse_frames(const orc_tree *t, const float *logp, int64_t frame_stri
   return ORC_OK;
 }
 
+/* ---- Two-stage greedy token selection (Sec. II-C, adaptation for CTC and transducer models) ----
+ *
+ * Per hypothesis and decoding step:
+ *   stage 1  the best token WITHOUT boosting (first maximum of the acoustic row);
+ *            - it is the blank: emit it, go on to the next step (tree not consulted);
+ *            - CTC only: it repeats the label emitted on the previous frame: keep it, unboosted,
+ *              tree state unchanged (the tree consumed that label when it was first emitted);
+ *   stage 2  otherwise the remaining tokens -- non-blank, and for CTC also not the previous
+ *            label -- are re-weighted by the tree (Eq. 1) and the best of THAT set is emitted
+ *            (first maximum), advancing the tree state.
+ * mode: 0 = single-stage (the plain fused argmax above), 1 = two-stage (transducer),
+ *       2 = two-stage with the CTC repeat rule.  last_tokens[b] is the label of the previous
+ *       frame (any value outside [0, V) means "none"); ignored unless mode == 2.
+ */
+#define ORC_SELECT_FUSED 0
+#define ORC_SELECT_TWO_STAGE 1
+#define ORC_SELECT_TWO_STAGE_CTC 2
+
+int32_t orc_fuse_step_select(const orc_tree *t, const float *logp, int64_t row_stride, const int32_t *states_in,
+                             const int32_t *last_tokens, float alpha, int32_t B, int32_t mode, int32_t *tokens,
+                             int32_t *states_out, float *scores) {
+  if (mode == ORC_SELECT_FUSED)
+    return orc_fuse_step(t, logp, row_stride, states_in, alpha, B, tokens, states_out, scores);
+  if (mode != ORC_SELECT_TWO_STAGE && mode != ORC_SELECT_TWO_STAGE_CTC) return ORC_EINVAL;
+  for (int b = 0; b < B; ++b) if (states_in[b] < 0 || states_in[b] >= t->n) return ORC_ERANGE;
+#pragma omp parallel for schedule(static)
+  for (int b = 0; b < B; ++b) {
+    const float *row = logp + (size_t)b * row_stride;
+    int s = states_in[b];
+    int last = (mode == ORC_SELECT_TWO_STAGE_CTC && last_tokens) ? last_tokens[b] : -1;
+    /* stage 1: greedy selection without boosting */
+    int v0 = 0;
+    for (int v = 1; v < t->V; ++v) if (row[v] > row[v0]) v0 = v;
+    if (v0 == t->blank || (mode == ORC_SELECT_TWO_STAGE_CTC && v0 == last)) {
+      tokens[b] = v0; states_out[b] = s; scores[b] = row[v0];
+      continue;
+    }
+    /* stage 2: re-weight the rest and reselect from it */
+    int best_v = -1, best_next = s;
+    float best = 0.0f;
+    for (int v = 0; v < t->V; ++v) {
+      if (v == t->blank) continue;
+      if (mode == ORC_SELECT_TWO_STAGE_CTC && v == last) continue;
+      float sc; int nx;
+      query(t, s, v, &sc, &nx);
+      float boost = alpha * sc;
+      float fused = row[v] + boost;
+      if (best_v < 0 || fused > best) { best = fused; best_v = v; best_next = nx; }
+    }
+    tokens[b] = best_v; states_out[b] = best_next; scores[b] = best;
+  }
+  return ORC_OK;
+}
+
+/* T frames of the selection above; the previous label of frame f is the token emitted at frame
+   f - 1 (last0, or "none" when last0 is NULL, for the first frame). */
+int32_t orc_fuse_frames_select(const orc_tree *t, const float *logp, int64_t frame_stride, int64_t row_stride,
+                               const int32_t *states0, const int32_t *last0, float alpha, int32_t T, int32_t B,
+                               int32_t mode, int32_t *tokens, int32_t *states, float *scores) {
+  int32_t *cur = (int32_t *)malloc(sizeof(int32_t) * (size_t)(B > 0 ? B : 1));
+  int32_t *last = (int32_t *)malloc(sizeof(int32_t) * (size_t)(B > 0 ? B : 1));
+  if (!cur || !last) { free(cur); free(last); return ORC_ENOMEM; }
+  memcpy(cur, states0, sizeof(int32_t) * (size_t)B);
+  for (int b = 0; b < B; ++b) last[b] = last0 ? last0[b] : -1;
+  for (int f = 0; f < T; ++f) {
+    int rc = orc_fuse_step_select(t, logp + (size_t)f * frame_stride, row_stride, cur, last, alpha, B, mode,
+                                  tokens + (size_t)f * B, states + (size_t)f * B, scores + (size_t)f * B);
+    if (rc != ORC_OK) { free(cur); free(last); return rc; }
+    memcpy(cur, states + (size_t)f * B, sizeof(int32_t) * (size_t)B);
+    memcpy(last, tokens + (size_t)f * B, sizeof(int32_t) * (size_t)B);
+  }
+  free(cur); free(last);
+  return ORC_OK;
+}
+
 typedef struct { float total; int64_t idx; } cand;
 
 static int cmp_cand(const void *a, const void *b) {

@@ -18,6 +18,9 @@ _LIB = os.path.join(_HERE, "libpb_oracle.so")
 
 W_UNIFORM = 0
 W_LOGDEPTH = 1
+SELECT_FUSED = 0
+SELECT_TWO_STAGE = 1
+SELECT_TWO_STAGE_CTC = 2
 
 
 class OracleError(RuntimeError):
@@ -68,6 +71,12 @@ def _load():
     lib.orc_fuse_frames.restype = C.c_int32
     lib.orc_fuse_frames.argtypes = [C.c_void_p, f32p, C.c_int64, C.c_int64, i32p, C.c_float, C.c_int32,
                                     C.c_int32, i32p, i32p, f32p]
+    lib.orc_fuse_step_select.restype = C.c_int32
+    lib.orc_fuse_step_select.argtypes = [C.c_void_p, f32p, C.c_int64, i32p, i32p, C.c_float, C.c_int32, C.c_int32,
+                                         i32p, i32p, f32p]
+    lib.orc_fuse_frames_select.restype = C.c_int32
+    lib.orc_fuse_frames_select.argtypes = [C.c_void_p, f32p, C.c_int64, C.c_int64, i32p, i32p, C.c_float, C.c_int32,
+                                           C.c_int32, C.c_int32, i32p, i32p, f32p]
     lib.orc_fuse_step_beam.restype = C.c_int32
     lib.orc_fuse_step_beam.argtypes = [C.c_void_p, f32p, C.c_int64, f32p, i32p, C.c_float, C.c_int32,
                                        C.c_int32, i32p, i32p, i32p, f32p]
@@ -198,6 +207,40 @@ class OracleTree:
                                        _p(scores, C.c_float))
         if rc:
             raise OracleError(rc, "orc_fuse_frames")
+        return tokens, states, scores
+
+    def fuse_step_select(self, logp, states, last_tokens, alpha: float, mode: int):
+        """Two-stage greedy selection (Sec. II-C); last_tokens may be None (no previous label)."""
+        logp = _f32(logp)
+        states = _i32(states)
+        last = None if last_tokens is None else _i32(last_tokens)
+        B = states.shape[0]
+        assert logp.shape == (B, self.vocab_size)
+        tokens = np.empty(B, dtype=np.int32)
+        states_out = np.empty(B, dtype=np.int32)
+        scores = np.empty(B, dtype=np.float32)
+        rc = self._lib.orc_fuse_step_select(self._h, _p(logp, C.c_float), self.vocab_size, _p(states, C.c_int32),
+                                            _p(last, C.c_int32), alpha, B, mode, _p(tokens, C.c_int32),
+                                            _p(states_out, C.c_int32), _p(scores, C.c_float))
+        if rc:
+            raise OracleError(rc, "orc_fuse_step_select")
+        return tokens, states_out, scores
+
+    def fuse_frames_select(self, logp, states0, last0, alpha: float, mode: int):
+        """logp float32[T,B,V]; the previous label of frame t is the token of frame t-1 (last0 for t = 0)."""
+        logp = _f32(logp)
+        states0 = _i32(states0)
+        last = None if last0 is None else _i32(last0)
+        T, B, V = logp.shape
+        assert V == self.vocab_size and states0.shape == (B,)
+        tokens = np.empty((T, B), dtype=np.int32)
+        states = np.empty((T, B), dtype=np.int32)
+        scores = np.empty((T, B), dtype=np.float32)
+        rc = self._lib.orc_fuse_frames_select(self._h, _p(logp, C.c_float), B * V, V, _p(states0, C.c_int32),
+                                              _p(last, C.c_int32), alpha, T, B, mode, _p(tokens, C.c_int32),
+                                              _p(states, C.c_int32), _p(scores, C.c_float))
+        if rc:
+            raise OracleError(rc, "orc_fuse_frames_select")
         return tokens, states, scores
 
     def fuse_step_beam(self, logp, hyp_scores, states, alpha: float, U: int, K: int):
