@@ -48,6 +48,12 @@ enum pb_weight_mode {
                        (Sec. II-B, score distribution; Alg. 1 Stage 1, arc.score)                       */
 };
 
+enum pb_select_mode {
+  PB_SELECT_FUSED = 0,        /* one stage: arg-max of the fused row over the whole vocabulary          */
+  PB_SELECT_TWO_STAGE = 1,    /* two-stage greedy selection of transducer decoding (Sec. II-C)          */
+  PB_SELECT_TWO_STAGE_CTC = 2 /* the same with the CTC rule for repeated labels (Sec. II-C)             */
+};
+
 typedef struct {
   int32_t vocab_size;         /* V > 0                                                                  */
   int32_t blank_id;           /* in [0, V), or -1 for a blank-free vocabulary                           */
@@ -151,6 +157,35 @@ int pb_fuse_step(const pb_tree* tree, const float* d_logp, int64_t row_stride, c
 int pb_fuse_frames(const pb_tree* tree, const float* d_logp, int64_t frame_stride, int64_t row_stride,
                    const int32_t* d_states0, float alpha, int32_t T, int32_t B, int32_t* d_tokens,
                    int32_t* d_states, float* d_scores, void* hip_stream);
+
+/*
+ * pb_fuse_step_select / pb_fuse_frames_select -- the greedy step and the multi-frame decoder with the
+ * token selection rule of Sec. II-C ("two-stage token selection"), chosen by `mode`:
+ *   PB_SELECT_FUSED          exactly pb_fuse_step / pb_fuse_frames (d_last* ignored).
+ *   PB_SELECT_TWO_STAGE      stage 1: v0 = argmax_v d_logp[b, v] (lowest id among equal maxima), no
+ *                            boosting.  If v0 is the blank: token = blank, state unchanged,
+ *                            score = d_logp[b, blank]; the tree is not consulted.
+ *                            Stage 2 otherwise: token = argmax over v != blank of
+ *                            d_logp[b, v] + (alpha * score(state, v)) (lowest id among equal maxima),
+ *                            state = next(state, token), score = that fused value.
+ *   PB_SELECT_TWO_STAGE_CTC  additionally, with last = the label emitted for the hypothesis on the
+ *                            previous frame: if v0 == last the repeated label is kept as it is
+ *                            (token = v0, state unchanged, score = d_logp[b, v0], no boost), and
+ *                            stage 2 runs over v != blank and v != last.
+ *   Previous labels: pb_fuse_step_select reads d_last_tokens[b] (int32[B]; NULL or any value outside
+ *   [0, V) = no previous label; it may alias d_tokens, so a decoding loop can pass the same buffer);
+ *   pb_fuse_frames_select uses d_last0[b] for frame 0 (NULL = none) and the token of frame t-1 for
+ *   frame t.  With a blank-free tree PB_SELECT_TWO_STAGE equals PB_SELECT_FUSED.
+ *   All other arguments, outputs and error codes are those of pb_fuse_step / pb_fuse_frames;
+ *   PB_EINVAL also for an unknown mode.
+ */
+int pb_fuse_step_select(const pb_tree* tree, const float* d_logp, int64_t row_stride, const int32_t* d_states_in,
+                        const int32_t* d_last_tokens, float alpha, int32_t B, int32_t mode, int32_t* d_tokens,
+                        int32_t* d_states_out, float* d_scores, void* hip_stream);
+
+int pb_fuse_frames_select(const pb_tree* tree, const float* d_logp, int64_t frame_stride, int64_t row_stride,
+                          const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B,
+                          int32_t mode, int32_t* d_tokens, int32_t* d_states, float* d_scores, void* hip_stream);
 
 /*
  * pb_fuse_step_beam -- one beam-search step: expansion scores, pruning and the state gather by

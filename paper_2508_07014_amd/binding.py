@@ -15,9 +15,10 @@ from . import build as _build
 
 PB_OK, PB_EINVAL, PB_ERANGE, PB_ENOMEM, PB_EHIP, PB_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 PB_W_UNIFORM, PB_W_LOGDEPTH = 0, 1
+PB_SELECT_FUSED, PB_SELECT_TWO_STAGE, PB_SELECT_TWO_STAGE_CTC = 0, 1, 2
 
 EXPORTS = ["pb_build", "pb_free", "pb_info", "pb_host_arrays", "pb_state_prefix", "pb_score", "pb_fuse_step",
-           "pb_fuse_frames", "pb_fuse_step_beam", "pb_diag_chase", "pb_strerror"]
+           "pb_fuse_frames", "pb_fuse_step_select", "pb_fuse_frames_select", "pb_fuse_step_beam", "pb_diag_chase", "pb_strerror"]
 
 
 class PbError(RuntimeError):
@@ -83,6 +84,11 @@ def load():
     lib.pb_fuse_step.argtypes = [vp, vp, C.c_int64, vp, C.c_float, C.c_int32, vp, vp, vp, vp]
     lib.pb_fuse_frames.restype = C.c_int
     lib.pb_fuse_frames.argtypes = [vp, vp, C.c_int64, C.c_int64, vp, C.c_float, C.c_int32, C.c_int32, vp, vp, vp, vp]
+    lib.pb_fuse_step_select.restype = C.c_int
+    lib.pb_fuse_step_select.argtypes = [vp, vp, C.c_int64, vp, vp, C.c_float, C.c_int32, C.c_int32, vp, vp, vp, vp]
+    lib.pb_fuse_frames_select.restype = C.c_int
+    lib.pb_fuse_frames_select.argtypes = [vp, vp, C.c_int64, C.c_int64, vp, vp, C.c_float, C.c_int32, C.c_int32,
+                                          C.c_int32, vp, vp, vp, vp]
     lib.pb_fuse_step_beam.restype = C.c_int
     lib.pb_fuse_step_beam.argtypes = [vp, vp, C.c_int64, vp, vp, C.c_float, C.c_int32, C.c_int32, vp, vp, vp, vp, vp]
     lib.pb_diag_chase.restype = C.c_int
@@ -194,6 +200,20 @@ def pb_fuse_frames(tree: Tree, d_logp, frame_stride: int, row_stride: int, d_sta
     _check(load().pb_fuse_frames(tree.handle, _dptr(d_logp), frame_stride, row_stride, _dptr(d_states0), alpha, T, B,
                                  _dptr(d_tokens), _dptr(d_states), _dptr(d_scores), stream or None),
            "pb_fuse_frames")
+
+
+def pb_fuse_step_select(tree: Tree, d_logp, row_stride: int, d_states_in, d_last_tokens, alpha: float, B: int,
+                        mode: int, d_tokens, d_states_out, d_scores, stream: int = 0):
+    _check(load().pb_fuse_step_select(tree.handle, _dptr(d_logp), row_stride, _dptr(d_states_in),
+                                      _dptr(d_last_tokens), alpha, B, mode, _dptr(d_tokens), _dptr(d_states_out),
+                                      _dptr(d_scores), stream or None), "pb_fuse_step_select")
+
+
+def pb_fuse_frames_select(tree: Tree, d_logp, frame_stride: int, row_stride: int, d_states0, d_last0, alpha: float,
+                          T: int, B: int, mode: int, d_tokens, d_states, d_scores, stream: int = 0):
+    _check(load().pb_fuse_frames_select(tree.handle, _dptr(d_logp), frame_stride, row_stride, _dptr(d_states0),
+                                        _dptr(d_last0), alpha, T, B, mode, _dptr(d_tokens), _dptr(d_states),
+                                        _dptr(d_scores), stream or None), "pb_fuse_frames_select")
 
 
 def pb_fuse_step_beam(tree: Tree, d_logp, row_stride: int, d_hyp_scores, d_states_in, alpha: float, U: int, K: int,

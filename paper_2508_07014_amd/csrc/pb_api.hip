@@ -157,32 +157,50 @@ int pb_score(const pb_tree* tree, const int32_t* d_states, int32_t B, float* d_s
   return pb::launch_score(tree->dev, d_states, B, d_scores, d_next, static_cast<hipStream_t>(hip_stream));
 }
 
-int pb_fuse_step(const pb_tree* tree, const float* d_logp, int64_t row_stride, const int32_t* d_states_in,
-                 float alpha, int32_t B, int32_t* d_tokens, int32_t* d_states_out, float* d_scores,
-                 void* hip_stream) {
+int pb_fuse_step_select(const pb_tree* tree, const float* d_logp, int64_t row_stride, const int32_t* d_states_in,
+                        const int32_t* d_last_tokens, float alpha, int32_t B, int32_t mode, int32_t* d_tokens,
+                        int32_t* d_states_out, float* d_scores, void* hip_stream) {
   if (!on_device(tree) || B < 0) return PB_EINVAL;
+  if (mode != PB_SELECT_FUSED && mode != PB_SELECT_TWO_STAGE && mode != PB_SELECT_TWO_STAGE_CTC) return PB_EINVAL;
   if (B == 0) return PB_OK;
   if (!d_logp || !d_states_in || !d_tokens || !d_states_out || !d_scores) return PB_EINVAL;
   if (row_stride < tree->dev.vocab_size) return PB_EINVAL;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (pb::wave_path_ok(tree->dev, d_logp, 0, row_stride))
-    return pb::launch_step_wave(tree->dev, d_logp, row_stride, d_states_in, alpha, B, d_tokens, d_states_out, d_scores,
-                                static_cast<hipStream_t>(hip_stream));
-  return pb::launch_fuse(tree->dev, d_logp, 0, row_stride, d_states_in, alpha, 1, B, d_tokens, d_states_out,
-                         d_scores, static_cast<hipStream_t>(hip_stream));
+    return pb::launch_step_wave(tree->dev, d_logp, row_stride, d_states_in, d_last_tokens, alpha, B, mode, d_tokens,
+                                d_states_out, d_scores, stream);
+  return pb::launch_fuse(tree->dev, d_logp, 0, row_stride, d_states_in, d_last_tokens, alpha, 1, B, mode, d_tokens,
+                         d_states_out, d_scores, stream);
+}
+
+int pb_fuse_step(const pb_tree* tree, const float* d_logp, int64_t row_stride, const int32_t* d_states_in,
+                 float alpha, int32_t B, int32_t* d_tokens, int32_t* d_states_out, float* d_scores,
+                 void* hip_stream) {
+  return pb_fuse_step_select(tree, d_logp, row_stride, d_states_in, nullptr, alpha, B, PB_SELECT_FUSED, d_tokens,
+                             d_states_out, d_scores, hip_stream);
+}
+
+int pb_fuse_frames_select(const pb_tree* tree, const float* d_logp, int64_t frame_stride, int64_t row_stride,
+                          const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B,
+                          int32_t mode, int32_t* d_tokens, int32_t* d_states, float* d_scores, void* hip_stream) {
+  if (!on_device(tree) || B < 0 || T < 0) return PB_EINVAL;
+  if (mode != PB_SELECT_FUSED && mode != PB_SELECT_TWO_STAGE && mode != PB_SELECT_TWO_STAGE_CTC) return PB_EINVAL;
+  if (B == 0 || T == 0) return PB_OK;
+  if (!d_logp || !d_states0 || !d_tokens || !d_states || !d_scores) return PB_EINVAL;
+  if (row_stride < tree->dev.vocab_size || frame_stride < 0) return PB_EINVAL;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (pb::wave_path_ok(tree->dev, d_logp, frame_stride, row_stride))
+    return pb::launch_frames_wave(tree->dev, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, mode,
+                                  d_tokens, d_states, d_scores, stream);
+  return pb::launch_fuse(tree->dev, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, mode, d_tokens,
+                         d_states, d_scores, stream);
 }
 
 int pb_fuse_frames(const pb_tree* tree, const float* d_logp, int64_t frame_stride, int64_t row_stride,
                    const int32_t* d_states0, float alpha, int32_t T, int32_t B, int32_t* d_tokens,
                    int32_t* d_states, float* d_scores, void* hip_stream) {
-  if (!on_device(tree) || B < 0 || T < 0) return PB_EINVAL;
-  if (B == 0 || T == 0) return PB_OK;
-  if (!d_logp || !d_states0 || !d_tokens || !d_states || !d_scores) return PB_EINVAL;
-  if (row_stride < tree->dev.vocab_size || frame_stride < 0) return PB_EINVAL;
-  if (pb::wave_path_ok(tree->dev, d_logp, frame_stride, row_stride))
-    return pb::launch_frames_wave(tree->dev, d_logp, frame_stride, row_stride, d_states0, alpha, T, B, d_tokens,
-                                  d_states, d_scores, static_cast<hipStream_t>(hip_stream));
-  return pb::launch_fuse(tree->dev, d_logp, frame_stride, row_stride, d_states0, alpha, T, B, d_tokens, d_states,
-                         d_scores, static_cast<hipStream_t>(hip_stream));
+  return pb_fuse_frames_select(tree, d_logp, frame_stride, row_stride, d_states0, nullptr, alpha, T, B,
+                               PB_SELECT_FUSED, d_tokens, d_states, d_scores, hip_stream);
 }
 
 int pb_fuse_step_beam(const pb_tree* tree, const float* d_logp, int64_t row_stride, const float* d_hyp_scores,

@@ -153,12 +153,19 @@ __device__ __forceinline__ Cursor cursor_from_root_rec(const v8i& r) {
   return c;
 }
 
-// alpha * (p_root + root_score[v]) for the lane's 16 tokens; the blank column boosts by 0.
+// Selection rule (enum pb_select_mode): 0 = single-stage fused arg-max, 1 = two-stage, 2 = two-stage
+// with the CTC repeat rule (Sec. II-C).  In the two-stage modes the blank is never a candidate of
+// the boosted re-selection: its column carries NaN, which neither fmaxf nor an equality test ever
+// selects, so an excluded token costs nothing in the reductions.
+//
+// alpha * (p_root + root_score[v]) for the lane's 16 tokens; the blank column boosts by 0 (SEL == 0)
+// or is excluded (SEL != 0).
+template <int SEL>
 __device__ __forceinline__ void make_base_boost(int cb, int lane, int blank, float p_root, float alpha,
                                                 const float (&rw)[16], float (&c)[16]) {
 #pragma unroll
   for (int j = 0; j < 16; ++j) {
-    const float boost = (cb + tok_of(j, lane) == blank) ? 0.0f : __fadd_rn(p_root, rw[j]);
+    const float boost = (cb + tok_of(j, lane) == blank) ? (SEL == 0 ? 0.0f : NAN) : __fadd_rn(p_root, rw[j]);
     c[j] = __fmul_rn(alpha, boost);
   }
 }
@@ -189,19 +196,19 @@ __device__ __forceinline__ void store_row_lds(float* row, int lane, const float 
 __device__ __forceinline__ int first_token_equal(const float (&f)[16], const float (&g)[4], float M, int lane) {
   const u64 b0 = __ballot(g[0] == M), b1 = __ballot(g[1] == M), b2 = __ballot(g[2] == M), b3 = __ballot(g[3] == M);
   int gi;
-  u64 bm, e0, e1, e2, e3;
+  u64 bm, e0, e1, e2;  // the fourth token of a group needs no ballot: it is the one left
   if (b0) {
     gi = 0; bm = b0;
-    e0 = __ballot(f[0] == M); e1 = __ballot(f[1] == M); e2 = __ballot(f[2] == M); e3 = __ballot(f[3] == M);
+    e0 = __ballot(f[0] == M); e1 = __ballot(f[1] == M); e2 = __ballot(f[2] == M);
   } else if (b1) {
     gi = 1; bm = b1;
-    e0 = __ballot(f[4] == M); e1 = __ballot(f[5] == M); e2 = __ballot(f[6] == M); e3 = __ballot(f[7] == M);
+    e0 = __ballot(f[4] == M); e1 = __ballot(f[5] == M); e2 = __ballot(f[6] == M);
   } else if (b2) {
     gi = 2; bm = b2;
-    e0 = __ballot(f[8] == M); e1 = __ballot(f[9] == M); e2 = __ballot(f[10] == M); e3 = __ballot(f[11] == M);
+    e0 = __ballot(f[8] == M); e1 = __ballot(f[9] == M); e2 = __ballot(f[10] == M);
   } else if (b3) {
     gi = 3; bm = b3;
-    e0 = __ballot(f[12] == M); e1 = __ballot(f[13] == M); e2 = __ballot(f[14] == M); e3 = __ballot(f[15] == M);
+    e0 = __ballot(f[12] == M); e1 = __ballot(f[13] == M); e2 = __ballot(f[14] == M);
   } else {
     return 0;  // only with NaN inputs (precondition violation): stay in range
   }
@@ -211,145 +218,182 @@ __device__ __forceinline__ int first_token_equal(const float (&f)[16], const flo
   return 256 * gi + 4 * L + k;
 }
 
+__device__ __forceinline__ float max4(float a, float b, float c, float d) { return fmaxf(fmaxf(a, b), fmaxf(c, d)); }
+
+// Stage 1 of the two-stage rule on one chunk: the unboosted row maximum and its lowest token.
+__device__ __forceinline__ void plain_argmax(const float (&x)[16], int lane, float& M0, int& v0) {
+  float g[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) g[i] = max4(x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]);
+  M0 = ukey_val(wave_max_u(ukey(max4(g[0], g[1], g[2], g[3]))));
+  v0 = first_token_equal(x, g, M0, lane);
+}
+
 // ------------------------------------------------------------------------------------------------
 // One frame of a row with V <= 1024 (a single chunk).  `cur` is the hypothesis' state with its
 // record; on return it is the state after the chosen token.  Returns the token and fused value.
 //   x    lane's raw log-probs (registers);  c / c_p  cached base boosts and the p_root they are for
 //   rw   lane's root scores;  row / tag  this wave's LDS row copy and tags;  stamp  tag stamp counter
-template <typename Hook>
+//   last label of the previous frame (SEL == 2 only; any value outside [0, V) = none)
+template <int SEL>
 __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const float (&x)[16], float (&c)[16],
                                          float& c_p, const float (&rw)[16], float alpha, float* row, unsigned* tag,
-                                         unsigned& stamp, int lane, Hook&& after_arcs, float& out_val, int& out_tok) {
+                                         unsigned& stamp, int lane, int last, float& out_val, int& out_tok) {
+  if constexpr (SEL != 0) {
+    // stage 1: selection without boosting; a blank (or a CTC repeat) is emitted as it is
+    float M0;
+    int v0;
+    plain_argmax(x, lane, M0, v0);
+    if (v0 == t.blank || (SEL == 2 && v0 == last)) {
+      out_val = uniform_f(M0);
+      out_tok = uniform_i(v0);
+      return;
+    }
+  }
   const int s = cur.s;
   const Rec rec0 = cur.rec;
   if (__float_as_int(c_p) != __float_as_int(cur.p_root)) {
-    make_base_boost(0, lane, t.blank, cur.p_root, alpha, rw, c);
+    make_base_boost<SEL>(0, lane, t.blank, cur.p_root, alpha, rw, c);
     c_p = cur.p_root;
   }
-  // ---- early load: record of the next chain state ------------------------------------------------
   const bool chain = (s != 0);
   const bool multi = chain && rec0.fail != 0;
-  Rec nrec = rec0;
-  if (multi) nrec = load_rec(t, rec0.fail);
+  const Cursor start = cur;
+  // The CTC rule bars the previous label from the re-selection.  The frame is first decided with the
+  // label still in; only if it wins is the frame decided again with the label excluded (excl >= 0).
+  for (int excl = -1;;) {
+    // ---- early load: record of the next chain state ----------------------------------------------
+    Rec nrec = rec0;
+    if (multi) nrec = load_rec(t, rec0.fail);
 
-  // ---- base candidates ---------------------------------------------------------------------------
-  float f[16], g[4];
+    // ---- base candidates -------------------------------------------------------------------------
+    float f[16], g[4];
 #pragma unroll
-  for (int j = 0; j < 16; ++j) f[j] = __fadd_rn(x[j], c[j]);
+    for (int j = 0; j < 16; ++j) f[j] = __fadd_rn(x[j], c[j]);
+    if (SEL == 2 && excl >= 0) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) g[i] = fmaxf(fmaxf(f[4 * i], f[4 * i + 1]), fmaxf(f[4 * i + 2], f[4 * i + 3]));
-  const float M = ukey_val(wave_max_u(ukey(fmaxf(fmaxf(g[0], g[1]), fmaxf(g[2], g[3])))));
-  const int vb = first_token_equal(f, g, M, lane);
-  const v8i rr = t.root_rec[vb];  // record of the state the base winner leads to (speculative)
+      for (int j = 0; j < 16; ++j) f[j] = (tok_of(j, lane) == excl) ? NAN : f[j];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) g[i] = max4(f[4 * i], f[4 * i + 1], f[4 * i + 2], f[4 * i + 3]);
+    const float M = ukey_val(wave_max_u(ukey(max4(g[0], g[1], g[2], g[3]))));
+    const int vb = first_token_equal(f, g, M, lane);
+    const v8i rr = t.root_rec[vb];  // record of the state the base winner leads to (speculative)
 
-  // ---- arc candidates along the failure chain ----------------------------------------------------
-  float bf = -INFINITY;
-  int btok = INT_MAX, bchild = 0;
-  bool hit_vb = false;
-  if (chain) {
-    store_row_lds(row, lane, x);
-    unsigned st = 0;
-    if (multi) st = ++stamp;
-    Rec r = rec0;
-    float p = 0.0f;
-    int level = 0;
-    for (;;) {
-      for (int j0 = 0; j0 < r.count; j0 += 64) {
-        // every lane loads (the index is clamped into the row) so that the load and its use stay
-        // in one block; lanes past the end of the row are discarded by `valid`
-        const bool valid = j0 + lane < r.count;
-        const int j = min(j0 + lane, r.count - 1);
-        const ArcRec a = t.arc[r.begin + j];
-        const int tk = a.token;
-        bool shadowed = !valid;
-        if (multi) {
-          if (level > 0) shadowed = shadowed || (tag[tk] == st);  // a deeper chain state owns this token
-          if (valid) tag[tk] = st;
+    // ---- arc candidates along the failure chain --------------------------------------------------
+    float bf = -INFINITY;
+    int btok = INT_MAX, bchild = 0;
+    bool hit_vb = false;
+    if (chain) {
+      store_row_lds(row, lane, x);
+      unsigned st = 0;
+      if (multi) st = ++stamp;
+      Rec r = rec0;
+      float p = 0.0f;
+      int level = 0;
+      for (;;) {
+        for (int j0 = 0; j0 < r.count; j0 += 64) {
+          // every lane loads (the index is clamped into the row) so that the load and its use stay
+          // in one block; lanes past the end of the row are discarded by `valid`
+          const bool valid = j0 + lane < r.count;
+          const int j = min(j0 + lane, r.count - 1);
+          const ArcRec a = t.arc[r.begin + j];
+          const int tk = a.token;
+          bool shadowed = !valid;
+          if (SEL == 2) shadowed = shadowed || tk == excl;
+          if (multi) {
+            if (level > 0) shadowed = shadowed || (tag[tk] == st);  // a deeper chain state owns this token
+            if (valid) tag[tk] = st;
+          }
+          hit_vb = hit_vb || (valid && tk == vb);
+          const float fa = __fadd_rn(row[tk], __fmul_rn(alpha, __fadd_rn(p, a.score)));
+          if (!shadowed && (fa > bf || (fa == bf && tk < btok))) {
+            bf = fa;
+            btok = tk;
+            bchild = r.begin + j + 1;
+          }
         }
-        hit_vb = hit_vb || (valid && tk == vb);
-        const float fa = __fadd_rn(row[tk], __fmul_rn(alpha, __fadd_rn(p, a.score)));
-        if (!shadowed && (fa > bf || (fa == bf && tk < btok))) {
-          bf = fa;
-          btok = tk;
-          bchild = r.begin + j + 1;
-        }
+        p = __fadd_rn(p, r.backoff);
+        if (r.fail == 0) break;
+        r = nrec;
+        if (r.fail != 0) nrec = load_rec(t, r.fail);
+        ++level;
       }
-      p = __fadd_rn(p, r.backoff);
-      if (r.fail == 0) break;
-      r = nrec;
-      if (r.fail != 0) nrec = load_rec(t, r.fail);
-      ++level;
     }
-  }
-  after_arcs();
 
-  // ---- decision -----------------------------------------------------------------------------------
-  bool arc_wins = false;
-  int va = INT_MAX, achild = 0;
-  float MA = 0.0f;
-  float base_val = M;
-  int base_tok = vb;
-  const bool mine0 = btok != INT_MAX;
-  if (__ballot(mine0) != 0) {
-    MA = ukey_val(wave_max_u(mine0 ? ukey(bf) : 0u));
-    const bool mine = mine0 && bf == MA;
-    const u64 eq = __ballot(mine);
-    if ((eq & (eq - 1)) == 0) {  // one lane holds the maximum
-      const int L = first_lane(eq);
-      va = __builtin_amdgcn_readlane(btok, L);
-      achild = __builtin_amdgcn_readlane(bchild, L);
-    } else {
-      va = wave_min_nn(mine ? btok : INT_MAX);
-      achild = __builtin_amdgcn_readlane(bchild, first_lane(__ballot(mine && btok == va)));
-    }
-    const bool vb_overridden = __ballot(hit_vb) != 0;
-    if (MA > M) {
-      arc_wins = true;
-    } else if (!vb_overridden) {
-      arc_wins = (MA == M) && (va < vb);
-    } else {
-      // The base winner is shadowed by an arc that does not beat it: tag every overridden token and
-      // redo the base arg-max without them.
-      const unsigned st2 = ++stamp;
-      for (int xs = s; xs != 0;) {
-        const Rec r = load_rec(t, xs);
-        for (int j = lane; j < r.count; j += 64) tag[t.arc[r.begin + j].token] = st2;
-        xs = uniform_i(r.fail);
-      }
-      unsigned k[16], mk = 0u;
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        k[j] = (tag[tok_of(j, lane)] == st2) ? 0u : ukey(f[j]);
-        mk = max(mk, k[j]);
-      }
-      const unsigned Mk = wave_max_u(mk);
-      bool have_base = Mk != 0u;
-      if (have_base) {
-        base_val = ukey_val(Mk);
-        int l2 = INT_MAX;
-#pragma unroll
-        for (int j = 15; j >= 0; --j) l2 = (k[j] != 0u && f[j] == base_val) ? tok_of(j, lane) : l2;
-        base_tok = wave_min_nn(l2);
-        have_base = base_tok != INT_MAX;
-      }
-      arc_wins = !have_base || MA > base_val || (MA == base_val && va < base_tok);
-    }
-  }
-  if (arc_wins) {
-    out_val = MA;
-    out_tok = va;
-    cur = cursor_at(t, achild);
-  } else {
-    out_val = base_val;
-    out_tok = base_tok;
-    if (base_tok != t.blank) {  // the blank keeps the state
-      if (base_tok == vb) {
-        cur = cursor_from_root_rec(rr);
+    // ---- decision --------------------------------------------------------------------------------
+    bool arc_wins = false;
+    int va = INT_MAX, achild = 0;
+    float MA = 0.0f;
+    float base_val = M;
+    int base_tok = vb;
+    const bool mine0 = btok != INT_MAX;
+    if (__ballot(mine0) != 0) {
+      MA = ukey_val(wave_max_u(mine0 ? ukey(bf) : 0u));
+      const bool mine = mine0 && bf == MA;
+      const u64 eq = __ballot(mine);
+      if ((eq & (eq - 1)) == 0) {  // one lane holds the maximum
+        const int L = first_lane(eq);
+        va = __builtin_amdgcn_readlane(btok, L);
+        achild = __builtin_amdgcn_readlane(bchild, L);
       } else {
-        const v8i r2 = t.root_rec[base_tok];
-        cur = cursor_from_root_rec(r2);
+        va = wave_min_nn(mine ? btok : INT_MAX);
+        achild = __builtin_amdgcn_readlane(bchild, first_lane(__ballot(mine && btok == va)));
+      }
+      const bool vb_overridden = __ballot(hit_vb) != 0;
+      if (MA > M) {
+        arc_wins = true;
+      } else if (!vb_overridden) {
+        arc_wins = (MA == M) && (va < vb);
+      } else {
+        // The base winner is shadowed by an arc that does not beat it: tag every overridden token and
+        // redo the base arg-max without them (and without the excluded ones, which hold NaN).
+        const unsigned st2 = ++stamp;
+        for (int xs = s; xs != 0;) {
+          const Rec r = load_rec(t, xs);
+          for (int j = lane; j < r.count; j += 64) tag[t.arc[r.begin + j].token] = st2;
+          xs = uniform_i(r.fail);
+        }
+        unsigned k[16], mk = 0u;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const bool out = (tag[tok_of(j, lane)] == st2) || (SEL != 0 && f[j] != f[j]);
+          k[j] = out ? 0u : ukey(f[j]);
+          mk = max(mk, k[j]);
+        }
+        const unsigned Mk = wave_max_u(mk);
+        bool have_base = Mk != 0u;
+        if (have_base) {
+          base_val = ukey_val(Mk);
+          int l2 = INT_MAX;
+#pragma unroll
+          for (int j = 15; j >= 0; --j) l2 = (k[j] != 0u && f[j] == base_val) ? tok_of(j, lane) : l2;
+          base_tok = wave_min_nn(l2);
+          have_base = base_tok != INT_MAX;
+        }
+        arc_wins = !have_base || MA > base_val || (MA == base_val && va < base_tok);
       }
     }
+    if (arc_wins) {
+      out_val = MA;
+      out_tok = va;
+      cur = cursor_at(t, achild);
+    } else {
+      out_val = base_val;
+      out_tok = base_tok;
+      if (base_tok != t.blank) {  // the blank keeps the state
+        if (base_tok == vb) {
+          cur = cursor_from_root_rec(rr);
+        } else {
+          const v8i r2 = t.root_rec[base_tok];
+          cur = cursor_from_root_rec(r2);
+        }
+      }
+    }
+    out_tok = uniform_i(out_tok);
+    if (SEL != 2 || excl >= 0 || out_tok != last) break;
+    excl = last;  // the previous label won the re-selection: decide again without it
+    cur = start;
   }
   cur.s = uniform_i(cur.s);
   cur.rec.begin = uniform_i(cur.rec.begin);
@@ -358,7 +402,6 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
   cur.rec.backoff = uniform_f(cur.rec.backoff);
   cur.p_root = uniform_f(cur.p_root);
   out_val = uniform_f(out_val);
-  out_tok = uniform_i(out_tok);
 }
 
 __device__ __forceinline__ void fill_invalid(int B, int b, int f0, int f1, int32_t* tokens, int32_t* states,
@@ -371,15 +414,16 @@ __device__ __forceinline__ void fill_invalid(int B, int b, int f0, int f1, int32
   }
 }
 
-// Decodes frames [f0, f1) of hypothesis b (V <= 1024) starting in state s_in (a value that may still be
-// in flight from a load: it is first looked at after the row loads have been issued; an invalid
-// state marks the frames).  With COMPARE set,
-// stops after the first frame whose out-state equals the one already stored in `states` (the
-// stored trajectory is then valid from there on).
-template <bool COMPARE, bool FULL>
+// Decodes frames [f0, f1) of hypothesis b (V <= 1024) starting in state s_in with previous label
+// last_in (values that may still be in flight from a load: they are first looked at after the row
+// loads have been issued; an invalid state marks the frames).  With COMPARE set, stops after the
+// first frame whose outcome equals the one already stored -- the out-state in `states` and, under
+// the CTC rule where the label feeds the next frame, the token in `tokens` (the stored trajectory is
+// then valid from there on).
+template <bool COMPARE, bool FULL, int SEL>
 __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
                                               int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s_in,
-                                              int32_t* __restrict__ tokens, int32_t* __restrict__ states,
+                                              int last_in, int32_t* __restrict__ tokens, int32_t* __restrict__ states,
                                               float* __restrict__ scores, float* row, unsigned* tag, unsigned& stamp,
                                               int lane) {
   const int V = t.V;
@@ -388,13 +432,15 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
   load16<FULL>(t.root_score, 0, V, lane, 0.0f, rw);
   if (f0 < f1) load16<FULL>(rp, 0, V, lane, -INFINITY, buf[0]);
   const int s = uniform_i(s_in);
+  int last = -1;
+  if (SEL == 2) last = uniform_i(last_in);
   if (!valid_state(t, s)) {
     fill_invalid(B, b, f0, f1, tokens, states, scores, lane);
     return;
   }
   Cursor cur = cursor_at(t, s);
   float c_p = cur.p_root;
-  make_base_boost(0, lane, t.blank, c_p, alpha, rw, c);
+  make_base_boost<SEL>(0, lane, t.blank, c_p, alpha, rw, c);
   size_t o = static_cast<size_t>(f0) * B + b;
   bool stop = false;
   for (int fb = f0; fb < f1 && !stop; fb += 2) {
@@ -406,15 +452,19 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
         if (f + 1 < f1) load16<FULL>(rp + frame_stride, 0, V, lane, -INFINITY, buf[(u + 1) % 2]);
         float val;
         int tok;
-        frame_1k(t, cur, buf[u], c, c_p, rw, alpha, row, tag, stamp, lane, []() {}, val, tok);
-        int stored = 0;
-        if (COMPARE) stored = uniform_i(__hip_atomic_load(states + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        frame_1k<SEL>(t, cur, buf[u], c, c_p, rw, alpha, row, tag, stamp, lane, last, val, tok);
+        int stored = 0, stored_tok = 0;
+        if (COMPARE) {
+          stored = uniform_i(__hip_atomic_load(states + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+          if (SEL == 2) stored_tok = uniform_i(__hip_atomic_load(tokens + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        }
         if (lane == 0) {
           tokens[o] = tok;
           states[o] = cur.s;
           scores[o] = val;
         }
-        if (COMPARE && stored == cur.s) stop = true;
+        if (COMPARE && stored == cur.s && (SEL != 2 || stored_tok == tok)) stop = true;
+        if (SEL == 2) last = tok;
         rp += frame_stride;
         o += B;
       }
@@ -430,14 +480,20 @@ struct Win {  // wave-uniform result of one chunk or frame
   int next;
 };
 
+// `excl` (SEL == 2): a token barred from the selection, or -1.
+template <int SEL>
 __device__ __forceinline__ Win decide_chunk(const TreeView& t, int s, int cb, const float (&x)[16], const float (&c)[16],
-                                            float alpha, float* row, unsigned* tag, unsigned stamp, int lane) {
+                                            float alpha, float* row, unsigned* tag, unsigned stamp, int lane, int excl) {
   float f[16], g[4];
 #pragma unroll
   for (int j = 0; j < 16; ++j) f[j] = __fadd_rn(x[j], c[j]);
+  if (SEL == 2 && excl >= 0) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) g[i] = fmaxf(fmaxf(f[4 * i], f[4 * i + 1]), fmaxf(f[4 * i + 2], f[4 * i + 3]));
-  const float M = ukey_val(wave_max_u(ukey(fmaxf(fmaxf(g[0], g[1]), fmaxf(g[2], g[3])))));
+    for (int j = 0; j < 16; ++j) f[j] = (cb + tok_of(j, lane) == excl) ? NAN : f[j];
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) g[i] = max4(f[4 * i], f[4 * i + 1], f[4 * i + 2], f[4 * i + 3]);
+  const float M = ukey_val(wave_max_u(ukey(max4(g[0], g[1], g[2], g[3]))));
   const int vb = first_token_equal(f, g, M, lane);
 
   bool have_arcs = false;
@@ -455,8 +511,8 @@ __device__ __forceinline__ Win decide_chunk(const TreeView& t, int s, int cb, co
           const ArcRec a = t.arc[r.begin + j];
           const unsigned rel = static_cast<unsigned>(a.token - cb);
           if (rel < static_cast<unsigned>(kChunk)) {
-            bool shadowed = false;
-            if (level > 0) shadowed = (tag[rel] == stamp);  // a deeper chain state owns this token
+            bool shadowed = (SEL == 2 && a.token == excl);
+            if (level > 0) shadowed = shadowed || (tag[rel] == stamp);  // a deeper chain state owns this token
             tag[rel] = stamp;
             if (!shadowed) {
               const float fa = __fadd_rn(row[rel], __fmul_rn(alpha, __fadd_rn(p, a.score)));
@@ -496,7 +552,8 @@ __device__ __forceinline__ Win decide_chunk(const TreeView& t, int s, int cb, co
       unsigned k[16], mk = 0u;
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
-        k[j] = (tag[tok_of(j, lane)] == stamp) ? 0u : ukey(f[j]);
+        const bool out = (tag[tok_of(j, lane)] == stamp) || (SEL != 0 && f[j] != f[j]);
+        k[j] = out ? 0u : ukey(f[j]);
         mk = max(mk, k[j]);
       }
       const unsigned Mk = wave_max_u(mk);
@@ -524,13 +581,15 @@ __device__ __forceinline__ Win decide_chunk(const TreeView& t, int s, int cb, co
   return w;
 }
 
-template <bool COMPARE>
+template <bool COMPARE, int SEL>
 __device__ __forceinline__ void run_frames_multi(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
                                                  int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s_in,
-                                                 int32_t* __restrict__ tokens, int32_t* __restrict__ states,
+                                                 int last_in, int32_t* __restrict__ tokens, int32_t* __restrict__ states,
                                                  float* __restrict__ scores, float* row, unsigned* tag, unsigned& stamp,
                                                  int lane) {
   int s = uniform_i(s_in);
+  int last = -1;
+  if (SEL == 2) last = uniform_i(last_in);
   if (!valid_state(t, s)) {
     fill_invalid(B, b, f0, f1, tokens, states, scores, lane);
     return;
@@ -541,55 +600,81 @@ __device__ __forceinline__ void run_frames_multi(const TreeView& t, const float*
   size_t o = static_cast<size_t>(f0) * B + b;
   float x[2][16], rw[16], c[16];
   for (int f = f0; f < f1; ++f) {
-    const float p_root = uniform_f(t.p_root[s]);
     Win best{0.0f, -1, s};
-    load16<false>(rp, 0, V, lane, -INFINITY, x[0]);
-    for (int ch0 = 0; ch0 < nch; ch0 += 2) {
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int ch = ch0 + u;
-        if (ch < nch) {
-          if (ch + 1 < nch) load16<false>(rp, (ch + 1) * kChunk, V, lane, -INFINITY, x[(u + 1) % 2]);
-          load16<false>(t.root_score, ch * kChunk, V, lane, 0.0f, rw);
-          make_base_boost(ch * kChunk, lane, t.blank, p_root, alpha, rw, c);
-          const Win w = decide_chunk(t, s, ch * kChunk, x[u], c, alpha, row, tag, ++stamp, lane);
-          if (best.tok < 0 || w.val > best.val) best = w;  // chunks ascend, so ties keep the lower token
-          best.val = uniform_f(best.val);
-          best.tok = uniform_i(best.tok);
-          best.next = uniform_i(best.next);
+    bool decided = false;
+    if constexpr (SEL != 0) {
+      // stage 1: unboosted arg-max over the whole row; the chunks are read again (from cache) below
+      for (int ch = 0; ch < nch; ++ch) {
+        load16<false>(rp, ch * kChunk, V, lane, -INFINITY, x[0]);
+        float M0;
+        int v0;
+        plain_argmax(x[0], lane, M0, v0);
+        if (best.tok < 0 || M0 > best.val) {  // chunks ascend, so ties keep the lower token
+          best.val = uniform_f(M0);
+          best.tok = uniform_i(ch * kChunk + v0);
         }
       }
+      decided = best.tok == t.blank || (SEL == 2 && best.tok == last);
     }
-    int stored = 0;
-    if (COMPARE) stored = uniform_i(__hip_atomic_load(states + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    if (!decided) {
+      const float p_root = uniform_f(t.p_root[s]);
+      for (int excl = -1;;) {
+        best = Win{0.0f, -1, s};
+        load16<false>(rp, 0, V, lane, -INFINITY, x[0]);
+        for (int ch0 = 0; ch0 < nch; ch0 += 2) {
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            const int ch = ch0 + u;
+            if (ch < nch) {
+              if (ch + 1 < nch) load16<false>(rp, (ch + 1) * kChunk, V, lane, -INFINITY, x[(u + 1) % 2]);
+              load16<false>(t.root_score, ch * kChunk, V, lane, 0.0f, rw);
+              make_base_boost<SEL>(ch * kChunk, lane, t.blank, p_root, alpha, rw, c);
+              const Win w = decide_chunk<SEL>(t, s, ch * kChunk, x[u], c, alpha, row, tag, ++stamp, lane, excl);
+              if (best.tok < 0 || w.val > best.val) best = w;  // chunks ascend, so ties keep the lower token
+              best.val = uniform_f(best.val);
+              best.tok = uniform_i(best.tok);
+              best.next = uniform_i(best.next);
+            }
+          }
+        }
+        if (SEL != 2 || excl >= 0 || best.tok != last) break;
+        excl = last;  // the previous label won the re-selection: decide again without it
+      }
+    }
+    int stored = 0, stored_tok = 0;
+    if (COMPARE) {
+      stored = uniform_i(__hip_atomic_load(states + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+      if (SEL == 2) stored_tok = uniform_i(__hip_atomic_load(tokens + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    }
     if (lane == 0) {
       tokens[o] = best.tok;
       states[o] = best.next;
       scores[o] = best.val;
     }
     s = best.next;
-    if (COMPARE && stored == s) return;
+    if (COMPARE && stored == s && (SEL != 2 || stored_tok == best.tok)) return;
+    if (SEL == 2) last = best.tok;
     rp += frame_stride;
     o += B;
   }
 }
 
 // MODE 0: V == 1024, 1: V < 1024, 2: V > 1024 (multi-chunk).
-template <bool COMPARE, int MODE>
+template <bool COMPARE, int MODE, int SEL>
 __device__ __forceinline__ void run_frames(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
-                                           int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s,
+                                           int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s, int last,
                                            int32_t* __restrict__ tokens, int32_t* __restrict__ states,
                                            float* __restrict__ scores, float* row, unsigned* tag, unsigned& stamp,
                                            int lane) {
   if constexpr (MODE == 0)
-    run_frames_1k<COMPARE, true>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, tokens, states, scores, row,
-                                 tag, stamp, lane);
+    run_frames_1k<COMPARE, true, SEL>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, tokens, states,
+                                      scores, row, tag, stamp, lane);
   else if constexpr (MODE == 1)
-    run_frames_1k<COMPARE, false>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, tokens, states, scores,
-                                  row, tag, stamp, lane);
+    run_frames_1k<COMPARE, false, SEL>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, tokens, states,
+                                       scores, row, tag, stamp, lane);
   else
-    run_frames_multi<COMPARE>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, tokens, states, scores, row,
-                              tag, stamp, lane);
+    run_frames_multi<COMPARE, SEL>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, tokens, states,
+                                   scores, row, tag, stamp, lane);
 }
 
 __device__ __forceinline__ void clear_tags(unsigned* tag, int lane) {
@@ -597,12 +682,14 @@ __device__ __forceinline__ void clear_tags(unsigned* tag, int lane) {
   for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(tag + 256 * i + 4 * lane) = make_uint4(0u, 0u, 0u, 0u);
 }
 
-// Pass 1: chain (b, j) decodes segment j of hypothesis b; j = 0 starts from states0[b] (exact),
-// j > 0 from the root (speculative).  One wave per chain.
-template <int MODE>
-__global__ void __launch_bounds__(256) frames_spec_kernel(DeviceTree dt, const float* __restrict__ logp,
+// Pass 1: chain (b, j) decodes segment j of hypothesis b; j = 0 starts from states0[b] and the
+// caller's previous label (exact), j > 0 from the root with no previous label (speculative).
+// One wave per chain.
+template <int MODE, int SEL>
+__global__ void __launch_bounds__(256, 4) frames_spec_kernel(DeviceTree dt, const float* __restrict__ logp,
                                                           int64_t frame_stride, int64_t row_stride,
-                                                          const int32_t* __restrict__ states0, float alpha, int T, int B,
+                                                          const int32_t* __restrict__ states0,
+                                                          const int32_t* __restrict__ last0, float alpha, int T, int B,
                                                           int seg_len, int nseg, int32_t* __restrict__ tokens,
                                                           int32_t* __restrict__ states, float* __restrict__ scores) {
   extern __shared__ float lds[];
@@ -615,25 +702,28 @@ __global__ void __launch_bounds__(256) frames_spec_kernel(DeviceTree dt, const f
   clear_tags(tag, lane);
   const TreeView t = make_view(dt);
   const int f0 = j * seg_len, f1 = min(T, f0 + seg_len);
-  int s = 0;
-  if (j == 0) s = states0[b];
+  int s = 0, last = -1;
+  if (j == 0) {
+    s = states0[b];
+    if (SEL == 2 && last0 != nullptr) last = last0[b];
+  }
   unsigned stamp = 0;
-  run_frames<false, MODE>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, tokens, states, scores, row, tag,
-                          stamp, lane);
+  run_frames<false, MODE, SEL>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, tokens, states, scores,
+                               row, tag, stamp, lane);
 }
 
 // Pass 2: one workgroup per hypothesis; its waves share the segments j = 1 .. nseg-1.
-//   (a) segment j is re-run from the end state pass 1 left in segment j-1 until the stored
-//       trajectory is met;
-//   (b) wave 0 then compares, for all segments at once, the end state of segment j-1 with the
-//       state segment j was re-run from, and repairs mismatches in order the same way.
-template <int MODE>
+//   (a) segment j is re-run from the outcome pass 1 left at the end of segment j-1 (end state and,
+//       under the CTC rule, last label) until the stored trajectory is met;
+//   (b) wave 0 then compares, for all segments at once, the outcome at the end of segment j-1 with
+//       the one segment j was re-run from, and repairs mismatches in order the same way.
+template <int MODE, int SEL>
 __global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, const float* __restrict__ logp,
                                                           int64_t frame_stride, int64_t row_stride, float alpha, int T,
                                                           int B, int seg_len, int nseg, int32_t* __restrict__ tokens,
                                                           int32_t* __restrict__ states, float* __restrict__ scores) {
   extern __shared__ float lds[];
-  __shared__ int assumed[64];
+  __shared__ int assumed[64], assumed_tok[64];
   const int lane = threadIdx.x & 63, wave = uniform_i(threadIdx.x >> 6), nwaves = blockDim.x >> 6;
   const int b = blockIdx.x;
   float* row = lds + wave * 2 * kChunk;
@@ -641,19 +731,28 @@ __global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, const f
   clear_tags(tag, lane);
   const TreeView t = make_view(dt);
   unsigned stamp = 0;
-  auto rerun = [&](int seg, int s) {
+  auto rerun = [&](int seg, int s, int last) {
     const int f0 = seg * seg_len, f1 = min(T, f0 + seg_len);
-    run_frames<true, MODE>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, tokens, states, scores, row, tag,
-                           stamp, lane);
+    run_frames<true, MODE, SEL>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, tokens, states, scores,
+                                row, tag, stamp, lane);
   };
   auto end_state_of = [&](int seg) {  // state after the last frame of segment `seg`
     const int32_t* p = states + static_cast<size_t>((seg + 1) * seg_len - 1) * B + b;
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   };
+  auto end_token_of = [&](int seg) {  // label of the last frame of segment `seg`
+    if (SEL != 2) return -1;
+    const int32_t* p = tokens + static_cast<size_t>((seg + 1) * seg_len - 1) * B + b;
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  };
   for (int seg = 1 + wave; seg < nseg; seg += nwaves) {
-    const int s = end_state_of(seg - 1);  // consumed inside rerun, after its row loads are on their way
-    if (lane == 0) assumed[seg] = s;
-    rerun(seg, s);  // pass 1 assumed the root: a segment whose neighbour ended there meets at once
+    // consumed inside rerun, after its row loads are on their way
+    const int s = end_state_of(seg - 1), last = end_token_of(seg - 1);
+    if (lane == 0) {
+      assumed[seg] = s;
+      assumed_tok[seg] = last;
+    }
+    rerun(seg, s, last);  // pass 1 assumed the root: a segment whose neighbour ended there meets at once
   }
   __threadfence_block();
   __syncthreads();
@@ -662,22 +761,29 @@ __global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, const f
     for (;;) {
       const bool check = lane >= 1 && lane < nseg;
       const int have = check ? end_state_of(lane - 1) : 0;
+      const int have_tok = check ? end_token_of(lane - 1) : 0;
       const int want = check ? assumed[lane] : 0;
-      const u64 bad = __ballot(check && have != want) & ~done;
+      const int want_tok = check ? assumed_tok[lane] : 0;
+      const u64 bad = __ballot(check && (have != want || (SEL == 2 && have_tok != want_tok))) & ~done;
       if (bad == 0) break;
       const int seg = first_lane(bad);
       const int s = __builtin_amdgcn_readlane(have, seg);
-      if (lane == 0) assumed[seg] = s;
-      rerun(seg, s);
+      const int last = __builtin_amdgcn_readlane(have_tok, seg);
+      if (lane == 0) {
+        assumed[seg] = s;
+        assumed_tok[seg] = last;
+      }
+      rerun(seg, s, last);
       done |= (2ull << seg) - 1;  // segments up to `seg` are final now
     }
   }
 }
 
 // Single step: one wave per hypothesis, no speculation.
-template <int MODE>
+template <int MODE, int SEL>
 __global__ void __launch_bounds__(256) step_wave_kernel(DeviceTree dt, const float* __restrict__ logp, int64_t row_stride,
-                                                        const int32_t* __restrict__ states_in, float alpha, int B,
+                                                        const int32_t* __restrict__ states_in,
+                                                        const int32_t* __restrict__ last_in, float alpha, int B,
                                                         int32_t* __restrict__ tokens, int32_t* __restrict__ states_out,
                                                         float* __restrict__ scores) {
   extern __shared__ float lds[];
@@ -689,9 +795,11 @@ __global__ void __launch_bounds__(256) step_wave_kernel(DeviceTree dt, const flo
   clear_tags(tag, lane);
   const TreeView t = make_view(dt);
   const int s = states_in[b];
+  int last = -1;
+  if (SEL == 2 && last_in != nullptr) last = last_in[b];
   unsigned stamp = 0;
-  run_frames<false, MODE>(t, logp, 0, row_stride, alpha, B, b, 0, 1, s, tokens, states_out, scores, row, tag, stamp,
-                          lane);
+  run_frames<false, MODE, SEL>(t, logp, 0, row_stride, alpha, B, b, 0, 1, s, last, tokens, states_out, scores, row, tag,
+                               stamp, lane);
 }
 
 inline int mode_of(int V) { return V == kChunk ? 0 : (V < kChunk ? 1 : 2); }
@@ -707,27 +815,37 @@ bool wave_path_ok(const DeviceTree& t, const float* d_logp, int64_t frame_stride
          frame_stride % 4 == 0 && aligned16(d_logp) && aligned16(t.root_score);
 }
 
+// Expands to one launch per (MODE, SEL) pair; `mode` and `sel` are runtime values in 0..2.
+#define PB_DISPATCH(mode, sel, LAUNCH) \
+  switch ((mode) * 3 + (sel)) {        \
+    case 0: LAUNCH(0, 0); break;       \
+    case 1: LAUNCH(0, 1); break;       \
+    case 2: LAUNCH(0, 2); break;       \
+    case 3: LAUNCH(1, 0); break;       \
+    case 4: LAUNCH(1, 1); break;       \
+    case 5: LAUNCH(1, 2); break;       \
+    case 6: LAUNCH(2, 0); break;       \
+    case 7: LAUNCH(2, 1); break;       \
+    default: LAUNCH(2, 2); break;      \
+  }
+
 int launch_step_wave(const DeviceTree& t, const float* d_logp, int64_t row_stride, const int32_t* d_states_in,
-                     float alpha, int32_t B, int32_t* d_tokens, int32_t* d_states_out, float* d_scores,
-                     hipStream_t stream) {
+                     const int32_t* d_last, float alpha, int32_t B, int sel, int32_t* d_tokens, int32_t* d_states_out,
+                     float* d_scores, hipStream_t stream) {
   const int waves = B >= 1024 ? 4 : 1;  // few rows: spread them over as many CUs as possible
   const dim3 grid(static_cast<unsigned>((B + waves - 1) / waves)), block(static_cast<unsigned>(64 * waves));
   const size_t lds = static_cast<size_t>(waves) * 2 * kChunk * sizeof(float);
-#define PB_LAUNCH(MODE)                                                                                         \
-  hipLaunchKernelGGL(step_wave_kernel<MODE>, grid, block, lds, stream, t, d_logp, row_stride, d_states_in, alpha, B, \
-                     d_tokens, d_states_out, d_scores)
-  switch (mode_of(t.vocab_size)) {
-    case 0: PB_LAUNCH(0); break;
-    case 1: PB_LAUNCH(1); break;
-    default: PB_LAUNCH(2); break;
-  }
+#define PB_LAUNCH(MODE, SEL)                                                                                      \
+  hipLaunchKernelGGL((step_wave_kernel<MODE, SEL>), grid, block, lds, stream, t, d_logp, row_stride, d_states_in, \
+                     d_last, alpha, B, d_tokens, d_states_out, d_scores)
+  PB_DISPATCH(mode_of(t.vocab_size), sel, PB_LAUNCH)
 #undef PB_LAUNCH
   return hipGetLastError() == hipSuccess ? PB_OK : PB_EHIP;
 }
 
 int launch_frames_wave(const DeviceTree& t, const float* d_logp, int64_t frame_stride, int64_t row_stride,
-                       const int32_t* d_states0, float alpha, int32_t T, int32_t B, int32_t* d_tokens,
-                       int32_t* d_states, float* d_scores, hipStream_t stream) {
+                       const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B, int sel,
+                       int32_t* d_tokens, int32_t* d_states, float* d_scores, hipStream_t stream) {
   // Segments: enough concurrent chains to cover the memory latency, at most kMaxSegments per
   // hypothesis, at least kMinSegLen frames long.
   int nseg = (kTargetChains + B - 1) / B;
@@ -740,29 +858,21 @@ int launch_frames_wave(const DeviceTree& t, const float* d_logp, int64_t frame_s
   const int64_t blocks = (chains + waves - 1) / waves;
   if (blocks > INT32_MAX) return PB_EUNSUPPORTED;
   const size_t lds = static_cast<size_t>(waves) * 2 * kChunk * sizeof(float);
-#define PB_LAUNCH(MODE)                                                                                              \
-  hipLaunchKernelGGL(frames_spec_kernel<MODE>, dim3(static_cast<unsigned>(blocks)), dim3(64 * waves), lds, stream, t, \
-                     d_logp, frame_stride, row_stride, d_states0, alpha, T, B, seg_len, nseg, d_tokens, d_states,      \
-                     d_scores)
   const int mode = mode_of(t.vocab_size);
-  switch (mode) {
-    case 0: PB_LAUNCH(0); break;
-    case 1: PB_LAUNCH(1); break;
-    default: PB_LAUNCH(2); break;
-  }
+#define PB_LAUNCH(MODE, SEL)                                                                                        \
+  hipLaunchKernelGGL((frames_spec_kernel<MODE, SEL>), dim3(static_cast<unsigned>(blocks)), dim3(64 * waves), lds,   \
+                     stream, t, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, seg_len, nseg,   \
+                     d_tokens, d_states, d_scores)
+  PB_DISPATCH(mode, sel, PB_LAUNCH)
 #undef PB_LAUNCH
   if (hipGetLastError() != hipSuccess) return PB_EHIP;
   if (nseg > 1) {
     int fw = nseg - 1 < g_fix_waves ? nseg - 1 : g_fix_waves;
     const size_t lds2 = static_cast<size_t>(fw) * 2 * kChunk * sizeof(float);
-#define PB_LAUNCH(MODE)                                                                                          \
-  hipLaunchKernelGGL(frames_fix_kernel<MODE>, dim3(static_cast<unsigned>(B)), dim3(64 * fw), lds2, stream, t, d_logp, \
-                     frame_stride, row_stride, alpha, T, B, seg_len, nseg, d_tokens, d_states, d_scores)
-    switch (mode) {
-      case 0: PB_LAUNCH(0); break;
-      case 1: PB_LAUNCH(1); break;
-      default: PB_LAUNCH(2); break;
-    }
+#define PB_LAUNCH(MODE, SEL)                                                                                      \
+  hipLaunchKernelGGL((frames_fix_kernel<MODE, SEL>), dim3(static_cast<unsigned>(B)), dim3(64 * fw), lds2, stream, \
+                     t, d_logp, frame_stride, row_stride, alpha, T, B, seg_len, nseg, d_tokens, d_states, d_scores)
+    PB_DISPATCH(mode, sel, PB_LAUNCH)
 #undef PB_LAUNCH
     if (hipGetLastError() != hipSuccess) return PB_EHIP;
   }
@@ -779,9 +889,11 @@ int prepare_wave_kernels() {
   if (waves > 8) {
     const int bytes = waves * 2 * kChunk * 4;
     const hipFuncAttribute attr = hipFuncAttributeMaxDynamicSharedMemorySize;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(frames_fix_kernel<0>), attr, bytes) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void*>(frames_fix_kernel<1>), attr, bytes) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void*>(frames_fix_kernel<2>), attr, bytes) != hipSuccess) {
+    bool ok = true;
+#define PB_SET(MODE, SEL)   ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(frames_fix_kernel<MODE, SEL>), attr, bytes) == hipSuccess
+    for (int ms = 0; ms < 9; ++ms) PB_DISPATCH(ms / 3, ms % 3, PB_SET)
+#undef PB_SET
+    if (!ok) {
       (void)hipGetLastError();
       waves = 8;
     }

@@ -152,9 +152,12 @@ __global__ void __launch_bounds__(256) score_kernel(DeviceTree t, const int32_t*
 // Fused row: boost row in LDS, Eq. 1 per token, per-thread running best.  All threads of the
 // workgroup must call it (barriers inside).  On return (best, best_v, best_next) is the thread's
 // own partial result; best_v < 0 if the thread saw no token.
+// Tokens equal to `excl_a` or `excl_b` are not candidates (-1 = none): the two-stage selection rules
+// bar the blank, and under the CTC rule the previous label, from the boosted re-selection.
 template <int VEC>
 __device__ __forceinline__ void fused_row(const DeviceTree& t, const float* __restrict__ lrow, int s, float alpha,
-                                          u64* row, int chunk, float& best, int& best_v, int& best_next) {
+                                          u64* row, int chunk, int excl_a, int excl_b, float& best, int& best_v,
+                                          int& best_next) {
   const int V = t.vocab_size;
   best = 0.0f;
   best_v = -1;
@@ -180,9 +183,10 @@ __device__ __forceinline__ void fused_row(const DeviceTree& t, const float* __re
           int nx;
           resolve(t, s, p_root, row[i + k], v0 + i + k, rsa[k], rna[k], sc, nx);
           const float fused = __fadd_rn(lpa[k], __fmul_rn(alpha, sc));
-          if (best_v < 0 || fused > best) {
+          const int v = v0 + i + k;
+          if (v != excl_a && v != excl_b && (best_v < 0 || fused > best)) {
             best = fused;
-            best_v = v0 + i + k;
+            best_v = v;
             best_next = nx;
           }
         }
@@ -193,9 +197,10 @@ __device__ __forceinline__ void fused_row(const DeviceTree& t, const float* __re
         int nx;
         resolve(t, s, p_root, row[i], v0 + i, t.root_score[v0 + i], t.root_next[v0 + i], sc, nx);
         const float fused = __fadd_rn(lrow[v0 + i], __fmul_rn(alpha, sc));
-        if (best_v < 0 || fused > best) {
+        const int v = v0 + i;
+        if (v != excl_a && v != excl_b && (best_v < 0 || fused > best)) {
           best = fused;
-          best_v = v0 + i;
+          best_v = v;
           best_next = nx;
         }
       }
@@ -203,20 +208,23 @@ __device__ __forceinline__ void fused_row(const DeviceTree& t, const float* __re
   }
 }
 
-// pb_fuse_step / pb_fuse_frames: one workgroup per hypothesis; T frames are walked in sequence with
-// the state carried in a register.
+// pb_fuse_step / pb_fuse_frames, any row shape: one workgroup per hypothesis; T frames are walked in
+// sequence with the state (and, under the CTC rule, the previous label) carried in registers.
+// sel: 0 single-stage, 1 two-stage, 2 two-stage with the CTC repeat rule (Sec. II-C).
 template <int VEC>
 __global__ void __launch_bounds__(1024) fuse_kernel(DeviceTree t, const float* __restrict__ logp, int64_t frame_stride,
                                                     int64_t row_stride, const int32_t* __restrict__ states0,
-                                                    float alpha, int T, int B, int32_t* __restrict__ tokens,
-                                                    int32_t* __restrict__ states, float* __restrict__ scores,
-                                                    int chunk) {
+                                                    const int32_t* __restrict__ last0, float alpha, int T, int B, int sel,
+                                                    int32_t* __restrict__ tokens, int32_t* __restrict__ states,
+                                                    float* __restrict__ scores, int chunk) {
   extern __shared__ u64 row[];
   __shared__ float sv[16];
   __shared__ int si[16];
   __shared__ int s_next;
   const int b = blockIdx.x;
+  const int V = t.vocab_size;
   int s = states0[b];
+  int last = (sel == 2 && last0 != nullptr) ? last0[b] : -1;
   for (int f = 0; f < T; ++f) {
     const size_t o = static_cast<size_t>(f) * B + b;
     if (static_cast<unsigned>(s) >= static_cast<unsigned>(t.num_states)) {
@@ -229,9 +237,32 @@ __global__ void __launch_bounds__(1024) fuse_kernel(DeviceTree t, const float* _
       continue;
     }
     const float* lrow = logp + static_cast<size_t>(f) * frame_stride + static_cast<size_t>(b) * row_stride;
+    if (sel != 0) {
+      // stage 1: arg-max of the acoustic row alone; a blank or a CTC repeat is emitted as it is
+      float m = 0.0f;
+      int mv = -1;
+      for (int v = threadIdx.x; v < V; v += blockDim.x) {
+        const float x = lrow[v];
+        if (mv < 0 || x > m) {
+          m = x;
+          mv = v;
+        }
+      }
+      block_best(m, mv, sv, si);
+      if (mv == t.blank_id || (sel == 2 && mv == last)) {
+        if (threadIdx.x == 0) {
+          tokens[o] = mv;
+          states[o] = s;
+          scores[o] = m;
+        }
+        last = mv;
+        continue;
+      }
+    }
     float best;
     int best_v, best_next;
-    fused_row<VEC>(t, lrow, s, alpha, row, chunk, best, best_v, best_next);
+    fused_row<VEC>(t, lrow, s, alpha, row, chunk, sel != 0 ? t.blank_id : -1, sel == 2 ? last : -1, best, best_v,
+                   best_next);
     float win = best;
     int win_v = best_v;
     block_best(win, win_v, sv, si);
@@ -243,6 +274,7 @@ __global__ void __launch_bounds__(1024) fuse_kernel(DeviceTree t, const float* _
     }
     __syncthreads();
     s = s_next;
+    last = win_v;
   }
 }
 
@@ -402,19 +434,19 @@ int launch_score(const DeviceTree& t, const int32_t* d_states, int32_t B, float*
 }
 
 int launch_fuse(const DeviceTree& t, const float* d_logp, int64_t frame_stride, int64_t row_stride,
-                const int32_t* d_states0, float alpha, int32_t T, int32_t B, int32_t* d_tokens, int32_t* d_states,
-                float* d_scores, hipStream_t stream) {
+                const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B, int sel,
+                int32_t* d_tokens, int32_t* d_states, float* d_scores, hipStream_t stream) {
   const int V = t.vocab_size;
   const int chunk = pick_chunk(V);
   const size_t lds = static_cast<size_t>(chunk) * sizeof(u64);
   const bool vec = (V % 4 == 0) && (row_stride % 4 == 0) && (frame_stride % 4 == 0) && aligned16(d_logp);
   const dim3 grid(static_cast<unsigned>(B)), block(static_cast<unsigned>(pick_threads(V)));
   if (vec)
-    hipLaunchKernelGGL(fuse_kernel<4>, grid, block, lds, stream, t, d_logp, frame_stride, row_stride, d_states0, alpha,
-                       T, B, d_tokens, d_states, d_scores, chunk);
+    hipLaunchKernelGGL(fuse_kernel<4>, grid, block, lds, stream, t, d_logp, frame_stride, row_stride, d_states0, d_last0,
+                       alpha, T, B, sel, d_tokens, d_states, d_scores, chunk);
   else
-    hipLaunchKernelGGL(fuse_kernel<1>, grid, block, lds, stream, t, d_logp, frame_stride, row_stride, d_states0, alpha,
-                       T, B, d_tokens, d_states, d_scores, chunk);
+    hipLaunchKernelGGL(fuse_kernel<1>, grid, block, lds, stream, t, d_logp, frame_stride, row_stride, d_states0, d_last0,
+                       alpha, T, B, sel, d_tokens, d_states, d_scores, chunk);
   return check_launch();
 }
 

@@ -12,10 +12,11 @@ constexpr int kScoreTile = 2048;  // tokens per workgroup of the score kernel (1
 int launch_score(const DeviceTree& t, const int32_t* d_states, int32_t B, float* d_scores, int32_t* d_next,
                  hipStream_t stream);
 
-// T == 1 with frame_stride == 0 is the single step.
+// T == 1 with frame_stride == 0 is the single step.  sel is an enum pb_select_mode value; d_last0 (previous
+// labels, CTC rule only) may be null.
 int launch_fuse(const DeviceTree& t, const float* d_logp, int64_t frame_stride, int64_t row_stride,
-                const int32_t* d_states0, float alpha, int32_t T, int32_t B, int32_t* d_tokens, int32_t* d_states,
-                float* d_scores, hipStream_t stream);
+                const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B, int sel,
+                int32_t* d_tokens, int32_t* d_states, float* d_scores, hipStream_t stream);
 
 // Wave-per-hypothesis greedy kernels (pb_frames.hip); usable when rows are 16-byte aligned and V % 4 == 0.
 constexpr int kTargetChains = 4096;  // concurrent decode chains aimed for by the multi-frame decoder
@@ -25,11 +26,11 @@ constexpr int kMaxSegments = 32;     // segments per hypothesis (one lane each i
 bool wave_path_ok(const DeviceTree& t, const float* d_logp, int64_t frame_stride, int64_t row_stride);
 int prepare_wave_kernels();  // once per device, after the device has been made current
 int launch_step_wave(const DeviceTree& t, const float* d_logp, int64_t row_stride, const int32_t* d_states_in,
-                     float alpha, int32_t B, int32_t* d_tokens, int32_t* d_states_out, float* d_scores,
-                     hipStream_t stream);
+                     const int32_t* d_last, float alpha, int32_t B, int sel, int32_t* d_tokens, int32_t* d_states_out,
+                     float* d_scores, hipStream_t stream);
 int launch_frames_wave(const DeviceTree& t, const float* d_logp, int64_t frame_stride, int64_t row_stride,
-                       const int32_t* d_states0, float alpha, int32_t T, int32_t B, int32_t* d_tokens,
-                       int32_t* d_states, float* d_scores, hipStream_t stream);
+                       const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B, int sel,
+                       int32_t* d_tokens, int32_t* d_states, float* d_scores, hipStream_t stream);
 
 // Latency probe: `hops` dependent loads through d_table (every entry a valid index into it).
 int launch_chase(const int32_t* d_table, int32_t start, int32_t hops, int32_t* d_out, hipStream_t stream);

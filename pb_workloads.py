@@ -180,6 +180,35 @@ def make_logp(cfg: Config, **kw) -> np.ndarray:
     return out
 
 
+def sticky_logp(seed: int, T: int, B: int, V: int, blank: int, sigma: float = 2.0, bump: float = 4.0,
+                p_repeat: float = 0.35, p_blank: float = 0.25, p_bump: float = 0.85,
+                grid: Optional[float] = 64.0) -> np.ndarray:
+    """CTC-shaped acoustic rows float32[T, B, V]: the arg-max path has blanks and repeated labels.
+
+    Every frame has a target label -- the previous frame's target again (p_repeat), the blank
+    (p_blank, if there is one) or a fresh uniform token -- whose N(0, sigma) logit is raised by
+    `bump` with probability p_bump.  With `grid` the values are rounded to multiples of 1/grid
+    (sums with dyadic boosts stay exact in fp32); with grid=None the rows are log-softmaxed.
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    x = rng.standard_normal((T, B, V)) * sigma
+    for b in range(B):
+        target = -1
+        for t in range(T):
+            r = rng.random()
+            if r < p_repeat and target >= 0:
+                pass
+            elif r < p_repeat + p_blank and blank >= 0:
+                target = blank
+            else:
+                target = int(rng.integers(0, V))
+            if rng.random() < p_bump:
+                x[t, b, target] += bump
+    if grid is None:
+        return log_softmax_rows(x)
+    return (np.round(x * grid) / grid).astype(np.float32)
+
+
 def sample_states(num_states: int, count: int, seed: int) -> np.ndarray:
     """States drawn uniformly from all tree states (deep failure chains included)."""
     rng = np.random.Generator(np.random.PCG64(seed))

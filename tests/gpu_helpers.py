@@ -4,8 +4,41 @@ import numpy as np
 import torch
 
 import paper_2508_07014_amd as pb
+import pb_workloads as W
+from oracle import OracleTree
+from oracle.pb_oracle import W_UNIFORM
 
 DEV = "cuda:0"
+TOL = 1e-5
+
+
+def build_both(tokens, offsets, V, blank, **kw):
+    ot = OracleTree(tokens, offsets, V, blank, weights=kw.get("weights"), weight_mode=kw.get("weight_mode", 0),
+                    beta=kw.get("beta", 2.0), unk_score=kw.get("unk_score", 0.0),
+                    final_zero_backoff=kw.get("final_zero_backoff", True))
+    tr = pb.pb_build(tokens, offsets, V, blank, device=0, **kw)
+    assert pb.pb_info(tr)["num_states"] == ot.num_states
+    return ot, tr
+
+
+_cache = {}
+
+
+def config_trees(idx, mode=W_UNIFORM):
+    key = (idx, mode)
+    if key not in _cache:
+        cfg = W.CONFIGS[idx]
+        toks, offs = W.make_phrases(cfg)
+        _cache[key] = (cfg, toks, offs) + build_both(toks, offs, cfg.vocab_size, cfg.blank_id, weight_mode=mode)
+    return _cache[key]
+
+
+def assert_scores(got, want):
+    assert got.shape == want.shape
+    fin = np.isfinite(want)
+    assert np.array_equal(got[~fin], want[~fin])          # -inf (dead beams) must match exactly
+    err = np.abs(got[fin].astype(np.float64) - want[fin].astype(np.float64))
+    assert err.size == 0 or err.max() <= TOL, float(err.max())
 
 
 def stream_ptr() -> int:

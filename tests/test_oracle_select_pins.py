@@ -24,23 +24,9 @@ def _phrases(tokens, offsets):
     return [tuple(int(x) for x in tokens[offsets[i]:offsets[i + 1]]) for i in range(len(offsets) - 1)]
 
 
-def _sticky_rows(seed, T, B, V, blank, grid=64.0):
+def _sticky_rows(seed, T, B, V, blank):
     """Acoustic rows on a dyadic grid whose arg-max path has blanks and repeated labels."""
-    rng = np.random.Generator(np.random.PCG64(seed))
-    x = rng.standard_normal((T, B, V)) * 2.0
-    for b in range(B):
-        target = -1
-        for t in range(T):
-            r = rng.random()
-            if r < 0.35 and target >= 0:
-                pass                                   # repeat the previous target
-            elif r < 0.6 and blank >= 0:
-                target = blank
-            else:
-                target = int(rng.integers(0, V))
-            if rng.random() < 0.85:
-                x[t, b, target] += 4.0
-    return (np.round(x * grid) / grid).astype(np.float32)
+    return W.sticky_logp(seed, T, B, V, blank)
 
 
 def _collapse(labels, blank, ctc):
