@@ -198,25 +198,34 @@ def main() -> int:
             chase[label] = {"ns_per_hop": ms * 1e6 / hops}
             del d_table, table, order
         extra["dependent_load_latency"] = chase
-        # structured variants of config 3 through the same entry point (parity checked)
-        variants = {"planted_20pct": dict(planting=W.Planting(toks, offs)),
+        # structured variants of config 3 through the same entry point, under the three selection rules
+        # (single-stage, two-stage, two-stage with the CTC repeat rule), each checked against the oracle
+        variants = {"as_written": {}, "planted_20pct": dict(planting=W.Planting(toks, offs)),
                     "blank_dominated_75pct": dict(blank_bias=8.0, blank_frac=0.75)}
+        modes = {"fused": pb.PB_SELECT_FUSED, "two_stage": pb.PB_SELECT_TWO_STAGE,
+                 "two_stage_ctc": pb.PB_SELECT_TWO_STAGE_CTC}
         results = {}
         for name, kw in variants.items():
-            lp = W.make_logp(cfg, **kw)
-            d_lp = torch.from_numpy(lp).to(dev)
-            fn = lambda: pb.pb_fuse_frames(tree, d_lp, B * V, V, d_s0, cfg.alpha, T, B, d_tok, d_st, d_sc, stream)
-            fn()
-            ms = _events(torch, fn, 5)
-            rec = {"ms": ms, "hyp_frames_per_s": B * T / (ms * 1e-3), "GBps": bytes_per_launch / (ms * 1e-3) / 1e9,
-                   "frac_hbm": bytes_per_launch / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
-            if not args.no_cpu:
-                w = ot.fuse_frames(lp, np.zeros(B, np.int32), cfg.alpha)
-                rec["parity"] = bool(np.array_equal(d_tok.cpu().numpy(), w[0]) and
-                                     np.array_equal(d_st.cpu().numpy(), w[1]))
-                rec["mean_state_depth_gt1_frac"] = float(np.mean(w[1] > info["root_degree"]))
-            results[name] = rec
-            del d_lp, lp
+            lp = logp if not kw else W.make_logp(cfg, **kw)
+            d_lp = d_logp if not kw else torch.from_numpy(lp).to(dev)
+            results[name] = {}
+            for mname, mode in modes.items():
+                fn = lambda: pb.pb_fuse_frames_select(tree, d_lp, B * V, V, d_s0, None, cfg.alpha, T, B, mode, d_tok,
+                                                      d_st, d_sc, stream)
+                fn()
+                ms = _events(torch, fn, 5)
+                rec = {"ms": ms, "hyp_frames_per_s": B * T / (ms * 1e-3),
+                       "GBps": bytes_per_launch / (ms * 1e-3) / 1e9,
+                       "frac_hbm": bytes_per_launch / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+                if not args.no_cpu:
+                    w = ot.fuse_frames_select(lp, np.zeros(B, np.int32), None, cfg.alpha, mode)
+                    rec["parity"] = bool(np.array_equal(d_tok.cpu().numpy(), w[0]) and
+                                         np.array_equal(d_st.cpu().numpy(), w[1]))
+                    rec["blank_frac"] = float(np.mean(w[0] == cfg.blank_id))
+                    rec["depth_ge2_frac"] = float(np.mean(w[1] > info["root_degree"]))
+                results[name][mname] = rec
+            if kw:
+                del d_lp, lp
         extra["config3_variants"] = results
         # one launch per frame (the RNN-T / AED shaped loop): states ping through a [T,B] buffer
         frames = min(T, 200)

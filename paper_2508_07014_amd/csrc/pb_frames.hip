@@ -13,8 +13,8 @@
 //    with ballots over the four 256-token groups.
 //  * Arc candidates.  The failure chain is walked with scalar loads (the state is wave-uniform);
 //    at each chain state the lanes take one arc each, gather its log-prob from the LDS copy of the
-//    row and evaluate Eq. 1 for it.  Chains with more than one state stamp a per-token LDS tag so
-//    that an arc shadowed by a deeper chain state is skipped.  If the base winner is itself an
+//    row and evaluate Eq. 1 for it.  Chains with more than one state mark each token in an LDS bit
+//    set so that an arc shadowed by a deeper chain state is skipped.  If the base winner is itself an
 //    overridden token and the arcs do not beat it, a second pass recomputes the base winner
 //    without the overridden tokens.
 //  * The record of the next state (arc range, failure link, backoffs) is fetched with the lookup
@@ -108,9 +108,21 @@ __device__ __forceinline__ unsigned wave_max_u(unsigned v) {
 __device__ __forceinline__ int wave_min_nn(int v) {
   return INT_MAX - static_cast<int>(wave_max_u(static_cast<unsigned>(INT_MAX - v)));
 }
+// The lane id again, but opaque to the optimiser: values derived from it inside a rarely taken branch
+// are then computed there instead of being hoisted out of the frame loop into long-lived registers.
+__device__ __forceinline__ int opaque(int v) {
+  asm volatile("" : "+v"(v));
+  return v;
+}
 __device__ __forceinline__ int first_lane(u64 mask) { return __builtin_ctzll(mask); }
 
 __device__ __forceinline__ int tok_of(int j, int lane) { return 256 * (j >> 2) + 4 * lane + (j & 3); }
+// Does the lane's slot j hold chunk-relative token `rel` (wave-uniform)?  Written so that the slot
+// test stays on the scalar side and no per-slot token ids have to live in vector registers.
+__device__ __forceinline__ bool slot_is(int j, int lane, int rel) {
+  const int slot = ((rel >> 8) << 2) | (rel & 3);  // uniform
+  return (slot == j) && (lane == ((rel >> 2) & 63)) && (static_cast<unsigned>(rel) < static_cast<unsigned>(kChunk));
+}
 
 __device__ __forceinline__ bool valid_state(const TreeView& t, int s) {
   return static_cast<unsigned>(s) < static_cast<unsigned>(t.num_states);
@@ -165,7 +177,7 @@ __device__ __forceinline__ void make_base_boost(int cb, int lane, int blank, flo
                                                 const float (&rw)[16], float (&c)[16]) {
 #pragma unroll
   for (int j = 0; j < 16; ++j) {
-    const float boost = (cb + tok_of(j, lane) == blank) ? (SEL == 0 ? 0.0f : NAN) : __fadd_rn(p_root, rw[j]);
+    const float boost = slot_is(j, lane, blank - cb) ? (SEL == 0 ? 0.0f : NAN) : __fadd_rn(p_root, rw[j]);
     c[j] = __fmul_rn(alpha, boost);
   }
 }
@@ -218,6 +230,15 @@ __device__ __forceinline__ int first_token_equal(const float (&f)[16], const flo
   return 256 * gi + 4 * L + k;
 }
 
+// Per-wave token marks: one bit per token of the current chunk (32 dwords of LDS).  LDS operations
+// of one wave execute in order, so clear -> set -> test needs no barrier inside the wave.
+constexpr int kTagWords = kChunk / 32;
+__device__ __forceinline__ void tags_clear(unsigned* bits, int lane) {
+  if (lane < kTagWords) bits[lane] = 0u;
+}
+__device__ __forceinline__ void tag_set(unsigned* bits, int tk) { atomicOr(&bits[tk >> 5], 1u << (tk & 31)); }
+__device__ __forceinline__ bool tag_test(const unsigned* bits, int tk) { return ((bits[tk >> 5] >> (tk & 31)) & 1u) != 0u; }
+
 __device__ __forceinline__ float max4(float a, float b, float c, float d) { return fmaxf(fmaxf(a, b), fmaxf(c, d)); }
 
 // Stage 1 of the two-stage rule on one chunk: the unboosted row maximum and its lowest token.
@@ -230,15 +251,38 @@ __device__ __forceinline__ void plain_argmax(const float (&x)[16], int lane, flo
 }
 
 // ------------------------------------------------------------------------------------------------
+// Base boosts of a row with V <= 1024 for the lane's 16 tokens; the root scores come from memory
+// (cache-resident) because they are needed only when the accumulated backoff of the state changes.
+template <bool FULL, int SEL>
+__device__ __forceinline__ void rebuild_base_boost(const TreeView& t, int lane, float p_root, float alpha,
+                                                   float (&c)[16]) {
+  const int ln = opaque(lane);
+  float rw[16];
+  load16<FULL>(t.root_score, 0, t.V, ln, 0.0f, rw);
+  make_base_boost<SEL>(0, ln, t.blank, p_root, alpha, rw, c);
+}
+
 // One frame of a row with V <= 1024 (a single chunk).  `cur` is the hypothesis' state with its
 // record; on return it is the state after the chosen token.  Returns the token and fused value.
-//   x    lane's raw log-probs (registers);  c / c_p  cached base boosts and the p_root they are for
-//   rw   lane's root scores;  row / tag  this wave's LDS row copy and tags;  stamp  tag stamp counter
-//   last label of the previous frame (SEL == 2 only; any value outside [0, V) = none)
-template <int SEL>
+//   x     lane's raw log-probs (registers); `next_row()` requests a later frame's row into other
+//         registers
+//   c / c_p  cached base boosts and the p_root they are for
+//   row / tags  this wave's LDS copy of the row and its token marks
+//   last  label of the previous frame (SEL == 2 only; any value outside [0, V) = none)
+template <bool FULL, int SEL, typename NextRow>
 __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const float (&x)[16], float (&c)[16],
-                                         float& c_p, const float (&rw)[16], float alpha, float* row, unsigned* tag,
-                                         unsigned& stamp, int lane, int last, float& out_val, int& out_tok) {
+                                         float& c_p, float alpha, float* row, unsigned* tags, int lane, int last,
+                                         NextRow&& next_row, float& out_val, int& out_tok) {
+  const int s = cur.s;
+  const Rec rec0 = cur.rec;
+  const bool chain = (s != 0);
+  const bool multi = chain && rec0.fail != 0;
+  // Vector loads retire in order, so a wait for arcs also waits for every row requested before them.
+  // The first 64 arcs of the state are therefore requested first and the row prefetch right after:
+  // the wait for these arcs leaves the prefetch in flight.
+  ArcRec a0{0, 0.0f};
+  if (chain && rec0.count > 0) a0 = t.arc[rec0.begin + min(lane, rec0.count - 1)];
+  next_row();
   if constexpr (SEL != 0) {
     // stage 1: selection without boosting; a blank (or a CTC repeat) is emitted as it is
     float M0;
@@ -250,14 +294,14 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
       return;
     }
   }
-  const int s = cur.s;
-  const Rec rec0 = cur.rec;
   if (__float_as_int(c_p) != __float_as_int(cur.p_root)) {
-    make_base_boost<SEL>(0, lane, t.blank, cur.p_root, alpha, rw, c);
+    rebuild_base_boost<FULL, SEL>(t, lane, cur.p_root, alpha, c);
     c_p = cur.p_root;
   }
-  const bool chain = (s != 0);
-  const bool multi = chain && rec0.fail != 0;
+  float f[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) f[j] = __fadd_rn(x[j], c[j]);
+  if (chain) store_row_lds(row, lane, x);
   const Cursor start = cur;
   // The CTC rule bars the previous label from the re-selection.  The frame is first decided with the
   // label still in; only if it wins is the frame decided again with the label excluded (excl >= 0).
@@ -267,12 +311,10 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
     if (multi) nrec = load_rec(t, rec0.fail);
 
     // ---- base candidates -------------------------------------------------------------------------
-    float f[16], g[4];
-#pragma unroll
-    for (int j = 0; j < 16; ++j) f[j] = __fadd_rn(x[j], c[j]);
+    float g[4];
     if (SEL == 2 && excl >= 0) {
 #pragma unroll
-      for (int j = 0; j < 16; ++j) f[j] = (tok_of(j, lane) == excl) ? NAN : f[j];
+      for (int j = 0; j < 16; ++j) f[j] = slot_is(j, opaque(lane), excl) ? NAN : f[j];
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) g[i] = max4(f[4 * i], f[4 * i + 1], f[4 * i + 2], f[4 * i + 3]);
@@ -285,9 +327,7 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
     int btok = INT_MAX, bchild = 0;
     bool hit_vb = false;
     if (chain) {
-      store_row_lds(row, lane, x);
-      unsigned st = 0;
-      if (multi) st = ++stamp;
+      if (multi) tags_clear(tags, lane);
       Rec r = rec0;
       float p = 0.0f;
       int level = 0;
@@ -297,13 +337,14 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
           // in one block; lanes past the end of the row are discarded by `valid`
           const bool valid = j0 + lane < r.count;
           const int j = min(j0 + lane, r.count - 1);
-          const ArcRec a = t.arc[r.begin + j];
+          ArcRec a = a0;
+          if (level != 0 || j0 != 0) a = t.arc[r.begin + j];
           const int tk = a.token;
           bool shadowed = !valid;
           if (SEL == 2) shadowed = shadowed || tk == excl;
           if (multi) {
-            if (level > 0) shadowed = shadowed || (tag[tk] == st);  // a deeper chain state owns this token
-            if (valid) tag[tk] = st;
+            if (level > 0) shadowed = shadowed || tag_test(tags, tk);  // a deeper chain state owns this token
+            if (valid) tag_set(tags, tk);
           }
           hit_vb = hit_vb || (valid && tk == vb);
           const float fa = __fadd_rn(row[tk], __fmul_rn(alpha, __fadd_rn(p, a.score)));
@@ -346,18 +387,19 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
       } else if (!vb_overridden) {
         arc_wins = (MA == M) && (va < vb);
       } else {
-        // The base winner is shadowed by an arc that does not beat it: tag every overridden token and
+        // The base winner is shadowed by an arc that does not beat it: mark every overridden token and
         // redo the base arg-max without them (and without the excluded ones, which hold NaN).
-        const unsigned st2 = ++stamp;
+        tags_clear(tags, lane);
         for (int xs = s; xs != 0;) {
           const Rec r = load_rec(t, xs);
-          for (int j = lane; j < r.count; j += 64) tag[t.arc[r.begin + j].token] = st2;
+          for (int j = lane; j < r.count; j += 64) tag_set(tags, t.arc[r.begin + j].token);
           xs = uniform_i(r.fail);
         }
+        const int ln = opaque(lane);
         unsigned k[16], mk = 0u;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-          const bool out = (tag[tok_of(j, lane)] == st2) || (SEL != 0 && f[j] != f[j]);
+          const bool out = tag_test(tags, tok_of(j, ln)) || (SEL != 0 && f[j] != f[j]);
           k[j] = out ? 0u : ukey(f[j]);
           mk = max(mk, k[j]);
         }
@@ -367,7 +409,7 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
           base_val = ukey_val(Mk);
           int l2 = INT_MAX;
 #pragma unroll
-          for (int j = 15; j >= 0; --j) l2 = (k[j] != 0u && f[j] == base_val) ? tok_of(j, lane) : l2;
+          for (int j = 15; j >= 0; --j) l2 = (k[j] != 0u && f[j] == base_val) ? tok_of(j, ln) : l2;
           base_tok = wave_min_nn(l2);
           have_base = base_tok != INT_MAX;
         }
@@ -420,17 +462,19 @@ __device__ __forceinline__ void fill_invalid(int B, int b, int f0, int f1, int32
 // first frame whose outcome equals the one already stored -- the out-state in `states` and, under
 // the CTC rule where the label feeds the next frame, the token in `tokens` (the stored trajectory is
 // then valid from there on).
+//   Rows travel through a ring of register buffers: the frame in hand and the one or two after it.
 template <bool COMPARE, bool FULL, int SEL>
 __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
                                               int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s_in,
                                               int last_in, int32_t* __restrict__ tokens, int32_t* __restrict__ states,
-                                              float* __restrict__ scores, float* row, unsigned* tag, unsigned& stamp,
-                                              int lane) {
+                                              float* __restrict__ scores, float* row, unsigned* tags, int lane) {
+  if (f0 >= f1) return;
   const int V = t.V;
   const float* rp = logp + static_cast<size_t>(b) * row_stride + static_cast<size_t>(f0) * frame_stride;
-  float buf[2][16], rw[16], c[16];
-  load16<FULL>(t.root_score, 0, V, lane, 0.0f, rw);
-  if (f0 < f1) load16<FULL>(rp, 0, V, lane, -INFINITY, buf[0]);
+  constexpr int NB = COMPARE ? 2 : 3;  // ring size: a re-run is short, one row ahead is enough there
+  float xb[NB][16], c[16];
+  load16<FULL>(rp, 0, V, lane, -INFINITY, xb[0]);
+  if (NB == 3 && f0 + 1 < f1) load16<FULL>(rp + frame_stride, 0, V, lane, -INFINITY, xb[1]);
   const int s = uniform_i(s_in);
   int last = -1;
   if (SEL == 2) last = uniform_i(last_in);
@@ -440,36 +484,67 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
   }
   Cursor cur = cursor_at(t, s);
   float c_p = cur.p_root;
-  make_base_boost<SEL>(0, lane, t.blank, c_p, alpha, rw, c);
+  rebuild_base_boost<FULL, SEL>(t, lane, c_p, alpha, c);
+  // Outputs.  The single-stage decode keeps those of up to 64 consecutive frames in the lanes (frame
+  // base + l in lane l) and writes them together, so that no store sits in the in-order queue of the
+  // loads; a re-run writes frame by frame, right after it has compared with what is stored, and so do
+  // the two-stage rules, whose extra state would otherwise push registers to scratch memory.
+  constexpr bool DEFER = !COMPARE && SEL == 0;
+  int base = f0;
+  int o_tok = 0, o_st = 0;
+  float o_sc = 0.0f;
+  auto flush = [&](int count) {
+    if (lane < count) {
+      const size_t o = static_cast<size_t>(base + lane) * B + b;
+      tokens[o] = o_tok;
+      states[o] = o_st;
+      scores[o] = o_sc;
+    }
+  };
   size_t o = static_cast<size_t>(f0) * B + b;
-  bool stop = false;
-  for (int fb = f0; fb < f1 && !stop; fb += 2) {
+  for (int fb = f0; fb < f1; fb += NB) {
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < NB; ++u) {
       const int f = fb + u;
-      if (f < f1 && !stop) {
-        // the next row is requested before this one is looked at
-        if (f + 1 < f1) load16<FULL>(rp + frame_stride, 0, V, lane, -INFINITY, buf[(u + 1) % 2]);
+      if (f < f1) {
+        const bool more = f + NB - 1 < f1;
+        const float* rpn = rp + (NB - 1) * frame_stride;
         float val;
         int tok;
-        frame_1k<SEL>(t, cur, buf[u], c, c_p, rw, alpha, row, tag, stamp, lane, last, val, tok);
-        int stored = 0, stored_tok = 0;
-        if (COMPARE) {
-          stored = uniform_i(__hip_atomic_load(states + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-          if (SEL == 2) stored_tok = uniform_i(__hip_atomic_load(tokens + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        frame_1k<FULL, SEL>(t, cur, xb[u], c, c_p, alpha, row, tags, lane, last,
+                            [&]() { if (more) load16<FULL>(rpn, 0, V, lane, -INFINITY, xb[(u + NB - 1) % NB]); }, val,
+                            tok);
+        if (!DEFER) {
+          int stored = -1, stored_tok = tok;
+          if (COMPARE) {
+            stored = uniform_i(__hip_atomic_load(states + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            if (SEL == 2) stored_tok = uniform_i(__hip_atomic_load(tokens + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+          }
+          if (lane == 0) {
+            tokens[o] = tok;
+            states[o] = cur.s;
+            scores[o] = val;
+          }
+          if (COMPARE && stored == cur.s && stored_tok == tok) return;
+          o += B;
+        } else {
+          const int slot = f - base;
+          if (lane == slot) {
+            o_tok = tok;
+            o_st = cur.s;
+            o_sc = val;
+          }
+          if (slot == 63) {
+            flush(64);
+            base = f + 1;
+          }
         }
-        if (lane == 0) {
-          tokens[o] = tok;
-          states[o] = cur.s;
-          scores[o] = val;
-        }
-        if (COMPARE && stored == cur.s && (SEL != 2 || stored_tok == tok)) stop = true;
         if (SEL == 2) last = tok;
         rp += frame_stride;
-        o += B;
       }
     }
   }
+  if (DEFER) flush(f1 - base);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -483,13 +558,13 @@ struct Win {  // wave-uniform result of one chunk or frame
 // `excl` (SEL == 2): a token barred from the selection, or -1.
 template <int SEL>
 __device__ __forceinline__ Win decide_chunk(const TreeView& t, int s, int cb, const float (&x)[16], const float (&c)[16],
-                                            float alpha, float* row, unsigned* tag, unsigned stamp, int lane, int excl) {
+                                            float alpha, float* row, unsigned* tags, int lane, int excl) {
   float f[16], g[4];
 #pragma unroll
   for (int j = 0; j < 16; ++j) f[j] = __fadd_rn(x[j], c[j]);
   if (SEL == 2 && excl >= 0) {
 #pragma unroll
-    for (int j = 0; j < 16; ++j) f[j] = (cb + tok_of(j, lane) == excl) ? NAN : f[j];
+    for (int j = 0; j < 16; ++j) f[j] = slot_is(j, lane, excl - cb) ? NAN : f[j];
   }
 #pragma unroll
   for (int i = 0; i < 4; ++i) g[i] = max4(f[4 * i], f[4 * i + 1], f[4 * i + 2], f[4 * i + 3]);
@@ -501,6 +576,7 @@ __device__ __forceinline__ Win decide_chunk(const TreeView& t, int s, int cb, co
   int btok = INT_MAX, bchild = 0;
   if (s != 0) {
     store_row_lds(row, lane, x);
+    tags_clear(tags, lane);
     float p = 0.0f;
     int xs = s, level = 0;
     while (xs != 0) {
@@ -512,8 +588,8 @@ __device__ __forceinline__ Win decide_chunk(const TreeView& t, int s, int cb, co
           const unsigned rel = static_cast<unsigned>(a.token - cb);
           if (rel < static_cast<unsigned>(kChunk)) {
             bool shadowed = (SEL == 2 && a.token == excl);
-            if (level > 0) shadowed = shadowed || (tag[rel] == stamp);  // a deeper chain state owns this token
-            tag[rel] = stamp;
+            if (level > 0) shadowed = shadowed || tag_test(tags, rel);  // a deeper chain state owns this token
+            tag_set(tags, rel);
             if (!shadowed) {
               const float fa = __fadd_rn(row[rel], __fmul_rn(alpha, __fadd_rn(p, a.score)));
               if (fa > bf || (fa == bf && static_cast<int>(rel) < btok)) {
@@ -543,7 +619,7 @@ __device__ __forceinline__ Win decide_chunk(const TreeView& t, int s, int cb, co
     const bool mine = mine0 && bf == MA;
     va = wave_min_nn(mine ? btok : INT_MAX);
     achild = __builtin_amdgcn_readlane(bchild, first_lane(__ballot(mine && btok == va)));
-    const bool vb_overridden = uniform_i(static_cast<int>(tag[vb] == stamp)) != 0;
+    const bool vb_overridden = uniform_i(static_cast<int>(tag_test(tags, vb))) != 0;
     if (MA > M) {
       arc_wins = true;
     } else if (!vb_overridden) {
@@ -552,7 +628,7 @@ __device__ __forceinline__ Win decide_chunk(const TreeView& t, int s, int cb, co
       unsigned k[16], mk = 0u;
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
-        const bool out = (tag[tok_of(j, lane)] == stamp) || (SEL != 0 && f[j] != f[j]);
+        const bool out = tag_test(tags, tok_of(j, lane)) || (SEL != 0 && f[j] != f[j]);
         k[j] = out ? 0u : ukey(f[j]);
         mk = max(mk, k[j]);
       }
@@ -585,8 +661,7 @@ template <bool COMPARE, int SEL>
 __device__ __forceinline__ void run_frames_multi(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
                                                  int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s_in,
                                                  int last_in, int32_t* __restrict__ tokens, int32_t* __restrict__ states,
-                                                 float* __restrict__ scores, float* row, unsigned* tag, unsigned& stamp,
-                                                 int lane) {
+                                                 float* __restrict__ scores, float* row, unsigned* tags, int lane) {
   int s = uniform_i(s_in);
   int last = -1;
   if (SEL == 2) last = uniform_i(last_in);
@@ -629,7 +704,7 @@ __device__ __forceinline__ void run_frames_multi(const TreeView& t, const float*
               if (ch + 1 < nch) load16<false>(rp, (ch + 1) * kChunk, V, lane, -INFINITY, x[(u + 1) % 2]);
               load16<false>(t.root_score, ch * kChunk, V, lane, 0.0f, rw);
               make_base_boost<SEL>(ch * kChunk, lane, t.blank, p_root, alpha, rw, c);
-              const Win w = decide_chunk<SEL>(t, s, ch * kChunk, x[u], c, alpha, row, tag, ++stamp, lane, excl);
+              const Win w = decide_chunk<SEL>(t, s, ch * kChunk, x[u], c, alpha, row, tags, lane, excl);
               if (best.tok < 0 || w.val > best.val) best = w;  // chunks ascend, so ties keep the lower token
               best.val = uniform_f(best.val);
               best.tok = uniform_i(best.tok);
@@ -664,23 +739,21 @@ template <bool COMPARE, int MODE, int SEL>
 __device__ __forceinline__ void run_frames(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
                                            int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s, int last,
                                            int32_t* __restrict__ tokens, int32_t* __restrict__ states,
-                                           float* __restrict__ scores, float* row, unsigned* tag, unsigned& stamp,
-                                           int lane) {
+                                           float* __restrict__ scores, float* row, unsigned* tags, int lane) {
   if constexpr (MODE == 0)
     run_frames_1k<COMPARE, true, SEL>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, tokens, states,
-                                      scores, row, tag, stamp, lane);
+                                      scores, row, tags, lane);
   else if constexpr (MODE == 1)
     run_frames_1k<COMPARE, false, SEL>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, tokens, states,
-                                       scores, row, tag, stamp, lane);
+                                       scores, row, tags, lane);
   else
     run_frames_multi<COMPARE, SEL>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, tokens, states,
-                                   scores, row, tag, stamp, lane);
+                                   scores, row, tags, lane);
 }
 
-__device__ __forceinline__ void clear_tags(unsigned* tag, int lane) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(tag + 256 * i + 4 * lane) = make_uint4(0u, 0u, 0u, 0u);
-}
+// LDS of one wave: a copy of the current row chunk and the token marks.
+constexpr int kWaveLdsFloats = kChunk + kTagWords;
+constexpr size_t kWaveLdsBytes = kWaveLdsFloats * sizeof(float);
 
 // Pass 1: chain (b, j) decodes segment j of hypothesis b; j = 0 starts from states0[b] and the
 // caller's previous label (exact), j > 0 from the root with no previous label (speculative).
@@ -697,9 +770,8 @@ __global__ void __launch_bounds__(256, 4) frames_spec_kernel(DeviceTree dt, cons
   const int chain = blockIdx.x * (blockDim.x >> 6) + wave;
   if (chain >= B * nseg) return;
   const int j = chain / B, b = chain - j * B;
-  float* row = lds + wave * 2 * kChunk;
-  unsigned* tag = reinterpret_cast<unsigned*>(row + kChunk);
-  clear_tags(tag, lane);
+  float* row = lds + wave * kWaveLdsFloats;
+  unsigned* tags = reinterpret_cast<unsigned*>(row + kChunk);
   const TreeView t = make_view(dt);
   const int f0 = j * seg_len, f1 = min(T, f0 + seg_len);
   int s = 0, last = -1;
@@ -707,9 +779,8 @@ __global__ void __launch_bounds__(256, 4) frames_spec_kernel(DeviceTree dt, cons
     s = states0[b];
     if (SEL == 2 && last0 != nullptr) last = last0[b];
   }
-  unsigned stamp = 0;
   run_frames<false, MODE, SEL>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, tokens, states, scores,
-                               row, tag, stamp, lane);
+                               row, tags, lane);
 }
 
 // Pass 2: one workgroup per hypothesis; its waves share the segments j = 1 .. nseg-1.
@@ -726,15 +797,13 @@ __global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, const f
   __shared__ int assumed[64], assumed_tok[64];
   const int lane = threadIdx.x & 63, wave = uniform_i(threadIdx.x >> 6), nwaves = blockDim.x >> 6;
   const int b = blockIdx.x;
-  float* row = lds + wave * 2 * kChunk;
-  unsigned* tag = reinterpret_cast<unsigned*>(row + kChunk);
-  clear_tags(tag, lane);
+  float* row = lds + wave * kWaveLdsFloats;
+  unsigned* tags = reinterpret_cast<unsigned*>(row + kChunk);
   const TreeView t = make_view(dt);
-  unsigned stamp = 0;
   auto rerun = [&](int seg, int s, int last) {
     const int f0 = seg * seg_len, f1 = min(T, f0 + seg_len);
     run_frames<true, MODE, SEL>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, tokens, states, scores,
-                                row, tag, stamp, lane);
+                                row, tags, lane);
   };
   auto end_state_of = [&](int seg) {  // state after the last frame of segment `seg`
     const int32_t* p = states + static_cast<size_t>((seg + 1) * seg_len - 1) * B + b;
@@ -790,23 +859,21 @@ __global__ void __launch_bounds__(256) step_wave_kernel(DeviceTree dt, const flo
   const int lane = threadIdx.x & 63, wave = uniform_i(threadIdx.x >> 6);
   const int b = blockIdx.x * (blockDim.x >> 6) + wave;
   if (b >= B) return;
-  float* row = lds + wave * 2 * kChunk;
-  unsigned* tag = reinterpret_cast<unsigned*>(row + kChunk);
-  clear_tags(tag, lane);
+  float* row = lds + wave * kWaveLdsFloats;
+  unsigned* tags = reinterpret_cast<unsigned*>(row + kChunk);
   const TreeView t = make_view(dt);
   const int s = states_in[b];
   int last = -1;
   if (SEL == 2 && last_in != nullptr) last = last_in[b];
-  unsigned stamp = 0;
-  run_frames<false, MODE, SEL>(t, logp, 0, row_stride, alpha, B, b, 0, 1, s, last, tokens, states_out, scores, row, tag,
-                               stamp, lane);
+  run_frames<false, MODE, SEL>(t, logp, 0, row_stride, alpha, B, b, 0, 1, s, last, tokens, states_out, scores, row, tags,
+                               lane);
 }
 
 inline int mode_of(int V) { return V == kChunk ? 0 : (V < kChunk ? 1 : 2); }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int g_fix_waves = 8;  // waves per fix-up workgroup the device's LDS allows (8 KiB each), set once
+int g_fix_waves = 8;  // waves per fix-up workgroup the device's LDS allows, set once
 
 }  // namespace
 
@@ -834,7 +901,7 @@ int launch_step_wave(const DeviceTree& t, const float* d_logp, int64_t row_strid
                      float* d_scores, hipStream_t stream) {
   const int waves = B >= 1024 ? 4 : 1;  // few rows: spread them over as many CUs as possible
   const dim3 grid(static_cast<unsigned>((B + waves - 1) / waves)), block(static_cast<unsigned>(64 * waves));
-  const size_t lds = static_cast<size_t>(waves) * 2 * kChunk * sizeof(float);
+  const size_t lds = static_cast<size_t>(waves) * kWaveLdsBytes;
 #define PB_LAUNCH(MODE, SEL)                                                                                      \
   hipLaunchKernelGGL((step_wave_kernel<MODE, SEL>), grid, block, lds, stream, t, d_logp, row_stride, d_states_in, \
                      d_last, alpha, B, d_tokens, d_states_out, d_scores)
@@ -857,7 +924,7 @@ int launch_frames_wave(const DeviceTree& t, const float* d_logp, int64_t frame_s
   const int waves = 4;
   const int64_t blocks = (chains + waves - 1) / waves;
   if (blocks > INT32_MAX) return PB_EUNSUPPORTED;
-  const size_t lds = static_cast<size_t>(waves) * 2 * kChunk * sizeof(float);
+  const size_t lds = static_cast<size_t>(waves) * kWaveLdsBytes;
   const int mode = mode_of(t.vocab_size);
 #define PB_LAUNCH(MODE, SEL)                                                                                        \
   hipLaunchKernelGGL((frames_spec_kernel<MODE, SEL>), dim3(static_cast<unsigned>(blocks)), dim3(64 * waves), lds,   \
@@ -868,7 +935,7 @@ int launch_frames_wave(const DeviceTree& t, const float* d_logp, int64_t frame_s
   if (hipGetLastError() != hipSuccess) return PB_EHIP;
   if (nseg > 1) {
     int fw = nseg - 1 < g_fix_waves ? nseg - 1 : g_fix_waves;
-    const size_t lds2 = static_cast<size_t>(fw) * 2 * kChunk * sizeof(float);
+    const size_t lds2 = static_cast<size_t>(fw) * kWaveLdsBytes;
 #define PB_LAUNCH(MODE, SEL)                                                                                      \
   hipLaunchKernelGGL((frames_fix_kernel<MODE, SEL>), dim3(static_cast<unsigned>(B)), dim3(64 * fw), lds2, stream, \
                      t, d_logp, frame_stride, row_stride, alpha, T, B, seg_len, nseg, d_tokens, d_states, d_scores)
@@ -880,14 +947,15 @@ int launch_frames_wave(const DeviceTree& t, const float* d_logp, int64_t frame_s
 }
 
 int prepare_wave_kernels() {
-  // The fix-up workgroup uses 8 KiB of dynamic LDS per wave; more than 8 waves need the limit raised.
+  // The fix-up workgroup uses kWaveLdsBytes of dynamic LDS per wave; past 64 KiB the limit must be raised.
   int dev = 0, max_lds = 0;
   if (hipGetDevice(&dev) != hipSuccess) return PB_EHIP;
   if (hipDeviceGetAttribute(&max_lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return PB_EHIP;
-  int waves = (max_lds - 1024) / (2 * kChunk * 4);
+  int waves = (max_lds - 1024) / static_cast<int>(kWaveLdsBytes);
   waves = waves > 16 ? 16 : (waves < 1 ? 1 : waves);
-  if (waves > 8) {
-    const int bytes = waves * 2 * kChunk * 4;
+  constexpr int kPlainLimit = 64 * 1024 - 1024;  // static LDS of the kernel included
+  if (waves * static_cast<int>(kWaveLdsBytes) > kPlainLimit) {
+    const int bytes = waves * static_cast<int>(kWaveLdsBytes);
     const hipFuncAttribute attr = hipFuncAttributeMaxDynamicSharedMemorySize;
     bool ok = true;
 #define PB_SET(MODE, SEL)   ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(frames_fix_kernel<MODE, SEL>), attr, bytes) == hipSuccess
@@ -895,7 +963,7 @@ int prepare_wave_kernels() {
 #undef PB_SET
     if (!ok) {
       (void)hipGetLastError();
-      waves = 8;
+      waves = kPlainLimit / static_cast<int>(kWaveLdsBytes);
     }
   }
   g_fix_waves = waves;

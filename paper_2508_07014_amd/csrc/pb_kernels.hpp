@@ -21,7 +21,7 @@ int launch_fuse(const DeviceTree& t, const float* d_logp, int64_t frame_stride, 
 // Wave-per-hypothesis greedy kernels (pb_frames.hip); usable when rows are 16-byte aligned and V % 4 == 0.
 constexpr int kTargetChains = 4096;  // concurrent decode chains aimed for by the multi-frame decoder
 constexpr int kMinSegLen = 8;        // shortest speculative segment, in frames
-constexpr int kMaxSegments = 32;     // segments per hypothesis (one lane each in the validation pass)
+constexpr int kMaxSegments = 64;     // segments per hypothesis (one lane each in the validation pass)
 
 bool wave_path_ok(const DeviceTree& t, const float* d_logp, int64_t frame_stride, int64_t row_stride);
 int prepare_wave_kernels();  // once per device, after the device has been made current
