@@ -61,6 +61,8 @@ typedef struct {
   int n;            /* number of states                                       */
   int V, blank;
   float c_unk;
+  int eos;          /* end-of-sentence token with heuristic scores (Sec. II-C), or -1      */
+  float c_eos;      /* final weight added to the EOS score at end-of-phrase states          */
   /* everything below is indexed by canonical state id */
   int *parent, *token, *depth, *fail, *is_final;
   double *acc, *arc;
@@ -174,7 +176,7 @@ orc_tree *orc_build(const int32_t *tokens, const int64_t *offsets, int64_t n_phr
 
   orc_tree *t = (orc_tree *)calloc(1, sizeof(orc_tree));
   if (!t) { free(nd); free(order); free(canon); free(tmp); *err = ORC_ENOMEM; return NULL; }
-  t->n = n; t->V = V; t->blank = blank; t->c_unk = c_unk;
+  t->n = n; t->V = V; t->blank = blank; t->c_unk = c_unk; t->eos = -1; t->c_eos = 0.0f;
   t->parent = (int *)malloc(sizeof(int) * (size_t)n);
   t->token = (int *)malloc(sizeof(int) * (size_t)n);
   t->depth = (int *)malloc(sizeof(int) * (size_t)n);
@@ -249,7 +251,7 @@ int32_t orc_child(const orc_tree *t, int32_t s, int32_t v) {
 
 /* ---- Stage 3: one (state, token) query by explicit failure-link chasing ---------- */
 
-static void query(const orc_tree *t, int s, int v, float *score, int *next) {
+static void tree_query(const orc_tree *t, int s, int v, float *score, int *next) {
   if (v == t->blank) { *score = 0.0f; *next = s; return; }
   float p = 0.0f;
   int x = s;
@@ -261,6 +263,41 @@ static void query(const orc_tree *t, int s, int v, float *score, int *next) {
   }
   if (c >= 0) { *score = p + t->arcw[c]; *next = c; }
   else        { *score = p + t->c_unk;   *next = 0; }
+}
+
+/* End-of-sentence heuristics for attention encoder-decoder models (Sec. II-C, the paragraph on the
+   EOS symbol).  The tree cannot score the EOS token itself, so that non-EOS boosts would suppress it.
+   The EOS score of a state is therefore
+     - the largest score the tree gives from this state to any other token (blank aside), and
+     - on top of it the final weight c_eos when the state is an end-of-phrase state, i.e. a whole
+       phrase has just been matched.
+   Taking the EOS ends the hypothesis: the state is left unchanged. */
+static void query(const orc_tree *t, int s, int v, float *score, int *next) {
+  if (t->eos >= 0 && v == t->eos) {
+    float best = 0.0f;
+    int have = 0;
+    for (int u = 0; u < t->V; ++u) {
+      if (u == t->eos || u == t->blank) continue;
+      float sc; int nx;
+      tree_query(t, s, u, &sc, &nx);
+      if (!have || sc > best) { best = sc; have = 1; }
+    }
+    float fw = t->is_final[s] ? t->c_eos : 0.0f;
+    *score = best + fw;
+    *next = s;
+    return;
+  }
+  tree_query(t, s, v, score, next);
+}
+
+/* Switches the EOS heuristics on (eos_id in [0, V), not the blank, not a token of any phrase) or off (-1). */
+int32_t orc_set_eos(orc_tree *t, int32_t eos_id, float final_eos_score) {
+  if (eos_id < -1 || eos_id >= t->V || (eos_id >= 0 && eos_id == t->blank)) return ORC_EINVAL;
+  if (eos_id >= 0)
+    for (int i = 1; i < t->n; ++i) if (t->token[i] == eos_id) return ORC_EINVAL;
+  t->eos = eos_id;
+  t->c_eos = final_eos_score;
+  return ORC_OK;
 }
 
 int32_t orc_query(const orc_tree *t, int32_t s, int32_t v, float *score, int32_t *next) {

@@ -62,6 +62,8 @@ def _load():
     lib.orc_node.argtypes = [C.c_void_p, C.c_int32, i32p, i32p, i32p, i32p, i32p, f64p, f32p, f32p]
     lib.orc_child.restype = C.c_int32
     lib.orc_child.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+    lib.orc_set_eos.restype = C.c_int32
+    lib.orc_set_eos.argtypes = [C.c_void_p, C.c_int32, C.c_float]
     lib.orc_query.restype = C.c_int32
     lib.orc_query.argtypes = [C.c_void_p, C.c_int32, C.c_int32, f32p, i32p]
     lib.orc_score.restype = C.c_int32
@@ -115,7 +117,7 @@ class OracleTree:
 
     def __init__(self, tokens, offsets, vocab_size: int, blank_id: int = 0, weights=None,
                  weight_mode: int = W_UNIFORM, beta: float = 2.0, unk_score: float = 0.0,
-                 final_zero_backoff: bool = True):
+                 final_zero_backoff: bool = True, eos_id: int = -1, final_eos_score: float = 0.0):
         lib = _load()
         self._lib = lib
         tokens = _i32(tokens)
@@ -128,8 +130,15 @@ class OracleTree:
                                 1 if final_zero_backoff else 0, C.byref(err))
         if not self._h:
             raise OracleError(err.value, "orc_build")
+        if eos_id != -1:
+            rc = lib.orc_set_eos(self._h, eos_id, final_eos_score)
+            if rc:
+                lib.orc_free(self._h)
+                self._h = None
+                raise OracleError(rc, "orc_set_eos")
         self.vocab_size = vocab_size
         self.blank_id = blank_id
+        self.eos_id = eos_id
         self.num_states = int(lib.orc_num_states(self._h))
         self.max_depth = int(lib.orc_max_depth(self._h))
 
