@@ -65,6 +65,11 @@ typedef struct {
                                  rule); 0: every state backs off with acc(fail) - acc(state)            */
   int32_t device;             /* HIP device ordinal to upload to; -1 = host-only tree (no GPU needed,
                                  step calls on it return PB_EINVAL)                                     */
+  int32_t eos_id;             /* end-of-sentence token of attention encoder-decoder models, or -1.  With
+                                 an EOS token, score(s, eos) = max over v != eos, v != blank of
+                                 score(s, v), plus final_eos_score if s is an end-of-phrase state, and
+                                 next(s, eos) = s (Sec. II-C, EOS heuristics); in every call               */
+  float final_eos_score;      /* the final weight of end-of-phrase states used by that rule             */
 } pb_build_opts;
 
 typedef struct {
@@ -75,6 +80,7 @@ typedef struct {
   int32_t root_degree;    /* tokens that start a phrase              */
   int32_t vocab_size;
   int32_t blank_id;
+  int32_t eos_id;         /* -1 if the tree has no EOS rule            */
   int64_t device_bytes;   /* size of the uploaded tree, 0 if host-only */
 } pb_tree_info;
 
@@ -102,7 +108,8 @@ typedef struct {
  *   and one-token phrases are legal; n_phrases == 0 gives a root-only tree.
  *   Host-synchronous.  On success *out receives the tree (free with pb_free); on failure *out is
  *   untouched.  PB_EINVAL: null argument, V <= 0, blank_id outside [-1, V), unknown weight_mode,
- *   offsets not strictly increasing (an empty phrase), a phrase containing blank_id.
+ *   offsets not strictly increasing (an empty phrase), a phrase containing blank_id or eos_id,
+ *   eos_id outside [-1, V) or equal to blank_id.
  *   PB_ERANGE: a token outside [0, V).  PB_EHIP / PB_ENOMEM: upload failed.
  */
 int pb_build(const int32_t* tokens, const int64_t* offsets, int64_t n_phrases, const float* weights,

@@ -30,13 +30,13 @@ class PbError(RuntimeError):
 class pb_build_opts(C.Structure):
     _fields_ = [("vocab_size", C.c_int32), ("blank_id", C.c_int32), ("weight_mode", C.c_int32),
                 ("beta", C.c_float), ("unk_score", C.c_float), ("final_zero_backoff", C.c_int32),
-                ("device", C.c_int32)]
+                ("device", C.c_int32), ("eos_id", C.c_int32), ("final_eos_score", C.c_float)]
 
 
 class pb_tree_info(C.Structure):
     _fields_ = [("num_states", C.c_int32), ("num_arcs", C.c_int32), ("max_depth", C.c_int32),
                 ("max_fail_chain", C.c_int32), ("root_degree", C.c_int32), ("vocab_size", C.c_int32),
-                ("blank_id", C.c_int32), ("device_bytes", C.c_int64)]
+                ("blank_id", C.c_int32), ("eos_id", C.c_int32), ("device_bytes", C.c_int64)]
 
 
 class pb_host_view(C.Structure):
@@ -136,12 +136,14 @@ class Tree:
 
 
 def pb_build(tokens, offsets, vocab_size: int, blank_id: int = 0, weights=None, weight_mode: int = PB_W_UNIFORM,
-             beta: float = 2.0, unk_score: float = 0.0, final_zero_backoff: bool = True, device: int = 0) -> Tree:
+             beta: float = 2.0, unk_score: float = 0.0, final_zero_backoff: bool = True, device: int = 0,
+             eos_id: int = -1, final_eos_score: float = 0.0) -> Tree:
     lib = load()
     tokens = np.ascontiguousarray(tokens, dtype=np.int32)
     offsets = np.ascontiguousarray(offsets, dtype=np.int64)
     w = None if weights is None else np.ascontiguousarray(weights, dtype=np.float32)
-    opts = pb_build_opts(vocab_size, blank_id, weight_mode, beta, unk_score, 1 if final_zero_backoff else 0, device)
+    opts = pb_build_opts(vocab_size, blank_id, weight_mode, beta, unk_score, 1 if final_zero_backoff else 0, device,
+                         eos_id, final_eos_score)
     out = C.c_void_p()
     rc = lib.pb_build(tokens.ctypes.data_as(C.POINTER(C.c_int32)), offsets.ctypes.data_as(C.POINTER(C.c_int64)),
                       len(offsets) - 1, None if w is None else w.ctypes.data_as(C.POINTER(C.c_float)),

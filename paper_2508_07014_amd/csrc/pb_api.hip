@@ -25,7 +25,9 @@ int upload(pb_tree* tr, int device) {
   const size_t n_rn = h.root_next.size() * sizeof(int32_t);
   const size_t n_pr = h.p_root.size() * sizeof(float);
   const size_t n_rr = h.root_rec.size() * sizeof(pb::RootRec);
-  const size_t total = padded(n_state) + padded(n_arc) + padded(n_rs) + padded(n_rn) + padded(n_pr) + padded(n_rr);
+  const size_t n_fs = h.final_score.size() * sizeof(float);
+  const size_t total =
+      padded(n_state) + padded(n_arc) + padded(n_rs) + padded(n_rn) + padded(n_pr) + padded(n_rr) + padded(n_fs);
   int prev = 0;
   if (hipGetDevice(&prev) != hipSuccess) { (void)hipGetLastError(); return PB_EHIP; }
   if (hipSetDevice(device) != hipSuccess) { (void)hipGetLastError(); return PB_EHIP; }
@@ -48,6 +50,8 @@ int upload(pb_tree* tr, int device) {
     tr->dev.root_next = static_cast<const int32_t*>(put(h.root_next.data(), n_rn));
     tr->dev.p_root = static_cast<const float*>(put(h.p_root.data(), n_pr));
     tr->dev.root_rec = static_cast<const pb::RootRec*>(put(h.root_rec.data(), n_rr));
+    tr->dev.final_score = n_fs ? static_cast<const float*>(put(h.final_score.data(), n_fs)) : nullptr;
+    tr->dev.eos_id = h.eos_id;
     if (rc == PB_OK) rc = pb::prepare_wave_kernels();
     tr->dev.num_states = static_cast<int32_t>(h.state.size());
     tr->dev.vocab_size = h.vocab_size;
@@ -113,6 +117,7 @@ int pb_info(const pb_tree* tree, pb_tree_info* out) {
   out->root_degree = h.root_degree;
   out->vocab_size = h.vocab_size;
   out->blank_id = h.blank_id;
+  out->eos_id = h.eos_id;
   out->device_bytes = tree->device_bytes;
   return PB_OK;
 }

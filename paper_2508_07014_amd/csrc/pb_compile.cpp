@@ -43,12 +43,13 @@ int compile_tree(const int32_t* tokens, const int64_t* offsets, int64_t n_phrase
   const int32_t V = o.vocab_size;
   if (V <= 0 || o.blank_id < -1 || o.blank_id >= V || n_phrases < 0) return PB_EINVAL;
   if (o.weight_mode != PB_W_UNIFORM && o.weight_mode != PB_W_LOGDEPTH) return PB_EINVAL;
+  if (o.eos_id < -1 || o.eos_id >= V || (o.eos_id >= 0 && o.eos_id == o.blank_id)) return PB_EINVAL;
   if (n_phrases > 0 && (!tokens || !offsets)) return PB_EINVAL;
   for (int64_t i = 0; i < n_phrases; ++i) {
     if (offsets[i] < 0 || offsets[i + 1] <= offsets[i]) return PB_EINVAL;
     for (int64_t j = offsets[i]; j < offsets[i + 1]; ++j) {
       if (tokens[j] < 0 || tokens[j] >= V) return PB_ERANGE;
-      if (tokens[j] == o.blank_id) return PB_EINVAL;
+      if (tokens[j] == o.blank_id || tokens[j] == o.eos_id) return PB_EINVAL;
     }
   }
   const int64_t total = n_phrases ? offsets[n_phrases] - offsets[0] : 0;
@@ -108,6 +109,7 @@ int compile_tree(const int32_t* tokens, const int64_t* offsets, int64_t n_phrase
     HostTree t;
     t.vocab_size = V;
     t.blank_id = o.blank_id;
+    t.eos_id = o.eos_id;
     t.arc_begin.assign(N, 0);
     t.arc_count.assign(N, 0);
     t.fail.assign(N, 0);
@@ -164,6 +166,11 @@ int compile_tree(const int32_t* tokens, const int64_t* offsets, int64_t n_phrase
       float p = 0.0f;
       for (int32_t x = s; x != 0; x = t.fail[x]) p = p + t.backoff[x];
       t.p_root[s] = p;
+    }
+    if (o.eos_id >= 0) {  // EOS rule (Sec. II-C): end-of-phrase states carry the final weight
+      t.final_score.assign(N, 0.0f);
+      for (int32_t s = 0; s < N; ++s)
+        if (t.is_final[s]) t.final_score[s] = o.final_eos_score;
     }
     t.root_score.assign(V, o.unk_score);
     t.root_next.assign(V, 0);

@@ -878,7 +878,8 @@ int g_fix_waves = 8;  // waves per fix-up workgroup the device's LDS allows, set
 }  // namespace
 
 bool wave_path_ok(const DeviceTree& t, const float* d_logp, int64_t frame_stride, int64_t row_stride) {
-  return t.p_root != nullptr && t.root_rec != nullptr && t.vocab_size % 4 == 0 && row_stride % 4 == 0 &&
+  // (the EOS rule needs the maximum of the whole boost row: such trees take the workgroup-per-row kernel)
+  return t.eos_id < 0 && t.p_root != nullptr && t.root_rec != nullptr && t.vocab_size % 4 == 0 && row_stride % 4 == 0 &&
          frame_stride % 4 == 0 && aligned16(d_logp) && aligned16(t.root_score);
 }
 

@@ -42,19 +42,21 @@ struct DeviceTree {
   const int32_t* root_next = nullptr;  // [V]
   const float* p_root = nullptr;       // [N] backoff accumulated from the state down to the root (fp32, chain order)
   const RootRec* root_rec = nullptr;   // [V]
+  const float* final_score = nullptr;  // [N] final weight of the EOS rule (0 for states that end no phrase); null without EOS
   int32_t num_states = 0;
   int32_t vocab_size = 0;
   int32_t blank_id = -1;
+  int32_t eos_id = -1;
 };
 
 struct HostTree {
-  int32_t vocab_size = 0, blank_id = -1;
+  int32_t vocab_size = 0, blank_id = -1, eos_id = -1;
   int32_t max_depth = 0, max_fail_chain = 0, root_degree = 0;
   std::vector<StateRec> state;
   std::vector<ArcRec> arc;
   std::vector<RootRec> root_rec;
   std::vector<int32_t> arc_begin, arc_count, fail, depth, parent, arc_token, root_next;
-  std::vector<float> backoff, arc_score, root_score, p_root;
+  std::vector<float> backoff, arc_score, root_score, p_root, final_score;
   std::vector<uint8_t> is_final;
   std::vector<double> acc;
 };

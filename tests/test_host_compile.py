@@ -184,3 +184,14 @@ def test_struct_layouts_match_header_field_order():
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
     fields = re.findall(r"(?:int32_t|int64_t)\s+(\w+);", body)
     assert fields == [n for n, _ in pb.binding.pb_tree_info._fields_]
+
+
+def test_eos_options_are_validated_and_reported():
+    toks, offs = np.array([1, 2, 3], np.int32), np.array([0, 3], np.int64)
+    for bad in (2, 0, 9, -2):            # inside a phrase, the blank, outside the vocabulary
+        with pytest.raises(pb.PbError) as e:
+            pb.pb_build(toks, offs, 6, 0, device=-1, eos_id=bad)
+        assert e.value.code == pb.PB_EINVAL
+    tr = pb.pb_build(toks, offs, 6, 0, device=-1, eos_id=5, final_eos_score=2.0)
+    assert pb.pb_info(tr)["eos_id"] == 5
+    assert pb.pb_info(pb.pb_build(toks, offs, 6, 0, device=-1))["eos_id"] == -1
