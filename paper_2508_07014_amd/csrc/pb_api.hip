@@ -221,6 +221,9 @@ int pb_fuse_step_beam(const pb_tree* tree, const float* d_logp, int64_t row_stri
   if (d_states_out == d_states_in) return PB_EINVAL;
   if (static_cast<int64_t>(K) * tree->dev.vocab_size >= INT32_MAX) return PB_EUNSUPPORTED;
   if (static_cast<int64_t>(U) * K > INT32_MAX) return PB_EUNSUPPORTED;
+  if (pb::beam_wave_ok(tree->dev, d_logp, row_stride, K))
+    return pb::launch_beam_wave(tree->dev, d_logp, row_stride, d_hyp_scores, d_states_in, alpha, U, K, d_tokens,
+                                d_parents, d_states_out, d_scores_out, static_cast<hipStream_t>(hip_stream));
   return pb::launch_beam(tree->dev, d_logp, row_stride, d_hyp_scores, d_states_in, alpha, U, K, d_tokens, d_parents,
                          d_states_out, d_scores_out, static_cast<hipStream_t>(hip_stream));
 }

@@ -869,6 +869,127 @@ __global__ void __launch_bounds__(256) step_wave_kernel(DeviceTree dt, const flo
                                lane);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Beam step, one wave per hypothesis row (V <= 1024, K <= kBeamWaveMaxK): the workgroup of an utterance
+// has K waves.  Every wave forms the fused row of its beam -- base candidates in registers, the arcs
+// of the failure chain scattered into an LDS overlay (value and child state per overridden token,
+// deepest chain state first, later ones skipped through the token marks) -- adds the hypothesis
+// score and extracts its K best totals in order by repeated wave arg-max (a taken entry becomes
+// NaN, which no maximum or equality test selects).  The K*K survivors meet in LDS, and wave 0
+// picks the utterance's K best by (total descending, flat index k*V+v ascending).
+constexpr int kBeamWaveMaxK = 8;
+constexpr int kBeamWaveLdsFloats = 2 * kChunk + kTagWords;                   // overlay values, overlay children, marks
+constexpr size_t kBeamCandBytes = kBeamWaveMaxK * kBeamWaveMaxK * 3 * sizeof(int);  // value, flat index, child
+
+template <bool FULL>
+__global__ void __launch_bounds__(64 * kBeamWaveMaxK) beam_wave_kernel(
+    DeviceTree dt, const float* __restrict__ logp, int64_t row_stride, const float* __restrict__ hyp,
+    const int32_t* __restrict__ states_in, float alpha, int K, int32_t* __restrict__ tokens,
+    int32_t* __restrict__ parents, int32_t* __restrict__ states_out, float* __restrict__ scores_out) {
+  extern __shared__ float lds[];
+  const int lane = threadIdx.x & 63, wave = uniform_i(threadIdx.x >> 6);
+  const int u = blockIdx.x, h = u * K + wave;
+  const TreeView t = make_view(dt);
+  const int V = t.V;
+  float* cand_val = lds;  // [K*K], then the flat indices and the children
+  int* cand_idx = reinterpret_cast<int*>(lds + kBeamWaveMaxK * kBeamWaveMaxK);
+  int* cand_nxt = cand_idx + kBeamWaveMaxK * kBeamWaveMaxK;
+  float* ov = lds + 3 * kBeamWaveMaxK * kBeamWaveMaxK + wave * kBeamWaveLdsFloats;
+  int* ov_next = reinterpret_cast<int*>(ov + kChunk);
+  unsigned* tags = reinterpret_cast<unsigned*>(ov + 2 * kChunk);
+
+  // an utterance with an invalid state is marked as a whole; every wave sees all K states
+  const int sk = states_in[u * K + min(lane, K - 1)];
+  if (__ballot(!valid_state(t, sk)) != 0) {
+    if (wave == 0 && lane < K) {
+      tokens[u * K + lane] = -1;
+      parents[u * K + lane] = -1;
+      states_out[u * K + lane] = -1;
+      scores_out[u * K + lane] = NAN;
+    }
+    return;
+  }
+  const int s = uniform_i(states_in[h]);
+  const float hs = uniform_f(hyp[h]);
+  const float* lrow = logp + static_cast<size_t>(h) * row_stride;
+  float x[16], c[16];
+  load16<FULL>(lrow, 0, V, lane, -INFINITY, x);
+  const Cursor cur = cursor_at(t, s);
+  rebuild_base_boost<FULL, 0>(t, lane, cur.p_root, alpha, c);
+  tags_clear(tags, lane);
+  // ---- overlay: arcs of the failure chain, deepest state first ------------------------------------
+  {
+    float p = 0.0f;
+    for (int xs = s; xs != 0;) {
+      const Rec r = load_rec(t, xs);
+      for (int j = lane; j < r.count; j += 64) {
+        const ArcRec a = t.arc[r.begin + j];
+        if (!tag_test(tags, a.token)) {  // tokens of one state are distinct: no lane races for an entry
+          tag_set(tags, a.token);
+          ov[a.token] = __fadd_rn(lrow[a.token], __fmul_rn(alpha, __fadd_rn(p, a.score)));
+          ov_next[a.token] = r.begin + j + 1;
+        }
+      }
+      p = __fadd_rn(p, r.backoff);
+      xs = uniform_i(r.fail);
+    }
+  }
+  // ---- totals of the lane's 16 tokens -------------------------------------------------------------
+  float tv[16];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int v0 = 256 * i + 4 * lane;
+    const unsigned bits = tags[v0 >> 5] >> (v0 & 31);
+    const float4 o = *reinterpret_cast<const float4*>(ov + v0);
+    const float oa[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float expansion = ((bits >> k) & 1u) ? oa[k] : __fadd_rn(x[4 * i + k], c[4 * i + k]);
+      // positions past V hold -inf: with at most V rounds the real tokens, which come first, are taken before them
+      tv[4 * i + k] = (FULL || v0 + k < V) ? __fadd_rn(hs, expansion) : -INFINITY;
+    }
+  }
+  // ---- the row's best totals, in order ---------------------------------------------------------------
+  const int rounds = min(K, V);
+  for (int r = 0; r < rounds; ++r) {
+    float g[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) g[i] = max4(tv[4 * i], tv[4 * i + 1], tv[4 * i + 2], tv[4 * i + 3]);
+    const float M = ukey_val(wave_max_u(ukey(max4(g[0], g[1], g[2], g[3]))));
+    const int v = uniform_i(first_token_equal(tv, g, M, lane));
+    int nx = s;  // the blank keeps the state
+    if (v != t.blank) nx = tag_test(tags, v) ? ov_next[v] : t.root_next[v];
+    if (lane == 0) {
+      cand_val[wave * K + r] = M;
+      cand_idx[wave * K + r] = wave * V + v;
+      cand_nxt[wave * K + r] = nx;
+    }
+    const int ln = opaque(lane);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) tv[j] = slot_is(j, ln, v) ? NAN : tv[j];
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  // ---- merge: one candidate per lane ------------------------------------------------------------------
+  const int n = K * rounds;
+  const bool have = lane < n;
+  float val = have ? cand_val[lane] : 0.0f;
+  const int idx = have ? cand_idx[lane] : INT_MAX;
+  const int nxt = have ? cand_nxt[lane] : 0;
+  bool live = have;
+  for (int j = 0; j < K; ++j) {
+    const float M = ukey_val(wave_max_u(live ? ukey(val) : 0u));
+    const int best = wave_min_nn((live && val == M) ? idx : INT_MAX);
+    if (live && idx == best) {
+      tokens[u * K + j] = idx % V;
+      parents[u * K + j] = idx / V;
+      states_out[u * K + j] = nxt;
+      scores_out[u * K + j] = val;
+      live = false;
+    }
+  }
+}
+
 inline int mode_of(int V) { return V == kChunk ? 0 : (V < kChunk ? 1 : 2); }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -947,6 +1068,26 @@ int launch_frames_wave(const DeviceTree& t, const float* d_logp, int64_t frame_s
   return PB_OK;
 }
 
+int g_beam_wave_max_k = 7;  // widest beam the wave kernel's LDS allows on the device, set once
+
+bool beam_wave_ok(const DeviceTree& t, const float* d_logp, int64_t row_stride, int32_t K) {
+  return wave_path_ok(t, d_logp, 0, row_stride) && t.vocab_size <= kChunk && K <= g_beam_wave_max_k;
+}
+
+int launch_beam_wave(const DeviceTree& t, const float* d_logp, int64_t row_stride, const float* d_hyp,
+                     const int32_t* d_states_in, float alpha, int32_t U, int32_t K, int32_t* d_tokens,
+                     int32_t* d_parents, int32_t* d_states_out, float* d_scores_out, hipStream_t stream) {
+  const size_t lds = kBeamCandBytes + static_cast<size_t>(K) * kBeamWaveLdsFloats * sizeof(float);
+  const dim3 grid(static_cast<unsigned>(U)), block(static_cast<unsigned>(64 * K));
+  if (t.vocab_size == kChunk)
+    hipLaunchKernelGGL(beam_wave_kernel<true>, grid, block, lds, stream, t, d_logp, row_stride, d_hyp, d_states_in,
+                       alpha, K, d_tokens, d_parents, d_states_out, d_scores_out);
+  else
+    hipLaunchKernelGGL(beam_wave_kernel<false>, grid, block, lds, stream, t, d_logp, row_stride, d_hyp, d_states_in,
+                       alpha, K, d_tokens, d_parents, d_states_out, d_scores_out);
+  return hipGetLastError() == hipSuccess ? PB_OK : PB_EHIP;
+}
+
 int prepare_wave_kernels() {
   // The fix-up workgroup uses kWaveLdsBytes of dynamic LDS per wave; past 64 KiB the limit must be raised.
   int dev = 0, max_lds = 0;
@@ -968,6 +1109,17 @@ int prepare_wave_kernels() {
     }
   }
   g_fix_waves = waves;
+  // The beam kernel with kBeamWaveMaxK waves needs a little more than 64 KiB.
+  const int beam_bytes = static_cast<int>(kBeamCandBytes + kBeamWaveMaxK * kBeamWaveLdsFloats * sizeof(float));
+  g_beam_wave_max_k = static_cast<int>((kPlainLimit - kBeamCandBytes) / (kBeamWaveLdsFloats * sizeof(float)));
+  if (beam_bytes <= max_lds) {
+    const hipFuncAttribute attr = hipFuncAttributeMaxDynamicSharedMemorySize;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(beam_wave_kernel<true>), attr, beam_bytes) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(beam_wave_kernel<false>), attr, beam_bytes) == hipSuccess)
+      g_beam_wave_max_k = kBeamWaveMaxK;
+    else
+      (void)hipGetLastError();
+  }
   return PB_OK;
 }
 

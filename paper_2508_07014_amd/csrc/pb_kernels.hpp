@@ -35,6 +35,12 @@ int launch_frames_wave(const DeviceTree& t, const float* d_logp, int64_t frame_s
 // Latency probe: `hops` dependent loads through d_table (every entry a valid index into it).
 int launch_chase(const int32_t* d_table, int32_t start, int32_t hops, int32_t* d_out, hipStream_t stream);
 
+// Wave-per-beam kernel (pb_frames.hip): rows as for the wave path, V <= 1024 and a beam the LDS can hold.
+bool beam_wave_ok(const DeviceTree& t, const float* d_logp, int64_t row_stride, int32_t K);
+int launch_beam_wave(const DeviceTree& t, const float* d_logp, int64_t row_stride, const float* d_hyp,
+                     const int32_t* d_states_in, float alpha, int32_t U, int32_t K, int32_t* d_tokens,
+                     int32_t* d_parents, int32_t* d_states_out, float* d_scores_out, hipStream_t stream);
+
 int launch_beam(const DeviceTree& t, const float* d_logp, int64_t row_stride, const float* d_hyp,
                 const int32_t* d_states_in, float alpha, int32_t U, int32_t K, int32_t* d_tokens, int32_t* d_parents,
                 int32_t* d_states_out, float* d_scores_out, hipStream_t stream);
