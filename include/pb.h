@@ -44,8 +44,12 @@ enum pb_status {
 
 enum pb_weight_mode {
   PB_W_UNIFORM = 0, /* every arc created by phrase i scores weights[i]                                  */
-  PB_W_LOGDEPTH = 1 /* depth 1: weights[i] (= c0); depth d > 1: weights[i] * beta + ln(d)
-                       (Sec. II-B, score distribution; Alg. 1 Stage 1, arc.score)                       */
+  PB_W_LOGDEPTH = 1, /* depth 1: weights[i] (= c0); depth d > 1: weights[i] * beta + ln(d)
+                        (Sec. II-B, score distribution; Alg. 1 Stage 1, arc.score)                      */
+  PB_W_UNIFORM_FINAL = 2 /* uniform arcs, and the arc into a state where a phrase ends additionally
+                        carries the sum of the uniform scores of the path root -> state: the uniform
+                        distribution with a reward at the final node that Sec. II-B describes and
+                        Sec. III-D compares with                                                        */
 };
 
 enum pb_select_mode {

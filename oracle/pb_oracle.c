@@ -44,6 +44,8 @@
 
 #define ORC_W_UNIFORM 0
 #define ORC_W_LOGDEPTH 1
+#define ORC_W_UNIFORM_FINAL 2 /* uniform arcs plus, on the arc into an end-of-phrase node, the accumulated
+                                 score of all its transitions (the variant the paper compares with, Sec. II-B, III-D) */
 
 typedef struct {
   int parent;      /* creation-order id of the parent, -1 for root           */
@@ -99,7 +101,7 @@ orc_tree *orc_build(const int32_t *tokens, const int64_t *offsets, int64_t n_phr
                     float c_unk, int32_t final_zero_backoff, int32_t *err) {
   *err = ORC_OK;
   if (V <= 0 || n_phrases < 0 || blank < -1 || blank >= V || (n_phrases > 0 && (!tokens || !offsets)) ||
-      (mode != ORC_W_UNIFORM && mode != ORC_W_LOGDEPTH)) {
+      (mode != ORC_W_UNIFORM && mode != ORC_W_LOGDEPTH && mode != ORC_W_UNIFORM_FINAL)) {
     *err = ORC_EINVAL;
     return NULL;
   }
@@ -129,7 +131,7 @@ orc_tree *orc_build(const int32_t *tokens, const int64_t *offsets, int64_t n_phr
       if (c < 0) {
         c = n++;
         nd[c].parent = cur; nd[c].token = tok; nd[c].depth = depth;
-        if (mode == ORC_W_UNIFORM) nd[c].arc = c0;
+        if (mode == ORC_W_UNIFORM || mode == ORC_W_UNIFORM_FINAL) nd[c].arc = c0;
         else nd[c].arc = (depth == 1) ? c0 : c0 * (double)beta + log((double)depth);
         nd[c].acc = nd[cur].acc + nd[c].arc;
         nd[c].is_final = 0; nd[c].fail = 0; nd[c].first_child = -1;
@@ -139,6 +141,21 @@ orc_tree *orc_build(const int32_t *tokens, const int64_t *offsets, int64_t n_phr
       cur = c;
     }
     nd[cur].is_final = 1;
+  }
+
+  if (mode == ORC_W_UNIFORM_FINAL) {
+    /* Which nodes end a phrase is known only now.  The arc into such a node gets, on top of its
+       uniform score, the sum of the uniform scores of all transitions from the root to the node;
+       accumulated scores are then rebuilt from the root (a parent is created before its children). */
+    double *plain = (double *)malloc(sizeof(double) * (size_t)n);
+    if (!plain) { free(nd); *err = ORC_ENOMEM; return NULL; }
+    plain[0] = 0.0;
+    for (int c = 1; c < n; ++c) {
+      plain[c] = plain[nd[c].parent] + nd[c].arc;
+      if (nd[c].is_final) nd[c].arc += plain[c];
+      nd[c].acc = nd[nd[c].parent].acc + nd[c].arc;
+    }
+    free(plain);
   }
 
   /* Breadth-first order with children by ascending token: this is the canonical numbering. */

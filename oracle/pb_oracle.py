@@ -18,6 +18,7 @@ _LIB = os.path.join(_HERE, "libpb_oracle.so")
 
 W_UNIFORM = 0
 W_LOGDEPTH = 1
+W_UNIFORM_FINAL = 2
 SELECT_FUSED = 0
 SELECT_TWO_STAGE = 1
 SELECT_TWO_STAGE_CTC = 2

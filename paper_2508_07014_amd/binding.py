@@ -14,7 +14,7 @@ import numpy as np
 from . import build as _build
 
 PB_OK, PB_EINVAL, PB_ERANGE, PB_ENOMEM, PB_EHIP, PB_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
-PB_W_UNIFORM, PB_W_LOGDEPTH = 0, 1
+PB_W_UNIFORM, PB_W_LOGDEPTH, PB_W_UNIFORM_FINAL = 0, 1, 2
 PB_SELECT_FUSED, PB_SELECT_TWO_STAGE, PB_SELECT_TWO_STAGE_CTC = 0, 1, 2
 
 EXPORTS = ["pb_build", "pb_free", "pb_info", "pb_host_arrays", "pb_state_prefix", "pb_score", "pb_fuse_step",

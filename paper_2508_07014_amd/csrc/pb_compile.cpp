@@ -42,7 +42,8 @@ int compile_tree(const int32_t* tokens, const int64_t* offsets, int64_t n_phrase
                  const pb_build_opts& o, HostTree& out) {
   const int32_t V = o.vocab_size;
   if (V <= 0 || o.blank_id < -1 || o.blank_id >= V || n_phrases < 0) return PB_EINVAL;
-  if (o.weight_mode != PB_W_UNIFORM && o.weight_mode != PB_W_LOGDEPTH) return PB_EINVAL;
+  if (o.weight_mode != PB_W_UNIFORM && o.weight_mode != PB_W_LOGDEPTH && o.weight_mode != PB_W_UNIFORM_FINAL)
+    return PB_EINVAL;
   if (o.eos_id < -1 || o.eos_id >= V || (o.eos_id >= 0 && o.eos_id == o.blank_id)) return PB_EINVAL;
   if (n_phrases > 0 && (!tokens || !offsets)) return PB_EINVAL;
   for (int64_t i = 0; i < n_phrases; ++i) {
@@ -86,6 +87,17 @@ int compile_tree(const int32_t* tokens, const int64_t* offsets, int64_t n_phrase
     }
     arcs.clear();
     const int32_t N = static_cast<int32_t>(nodes.size());
+    if (o.weight_mode == PB_W_UNIFORM_FINAL) {
+      // end-of-phrase reward: the arc into a node where a phrase ends also carries the uniform scores of
+      // the whole path (node ids grow from parent to child, so one forward sweep rebuilds acc)
+      std::vector<double> path(N, 0.0);
+      for (int32_t id = 1; id < N; ++id) {
+        TmpNode& nd = nodes[id];
+        path[id] = path[nd.parent] + nd.arc;
+        if (nd.is_final) nd.arc += path[id];
+        nd.acc = nodes[nd.parent].acc + nd.arc;
+      }
+    }
 
     // ---- canonical numbering: breadth-first, children by ascending token -------------
     std::vector<int32_t> by_parent(N > 1 ? N - 1 : 0);

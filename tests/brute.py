@@ -35,6 +35,7 @@ class BruteTree:
         self.arc: Dict[Tuple[int, ...], float] = {}
         self.acc: Dict[Tuple[int, ...], float] = {(): 0.0}
         beta64 = float(f32(beta))
+        plain: Dict[Tuple[int, ...], float] = {(): 0.0}
         for p, w in zip(self.phrases, weights):
             c0 = float(f32(w))
             for d in range(1, len(p) + 1):
@@ -43,6 +44,11 @@ class BruteTree:
                     continue
                 if mode == "uniform":
                     a = c0
+                elif mode == "uniform_final":
+                    # uniform arcs; the arc that completes a phrase also pays the uniform scores of all
+                    # transitions of that phrase (Sec. II-B: reward = accumulated score, final node only)
+                    plain[x] = plain[x[:-1]] + c0
+                    a = c0 + (plain[x] if x in self.finals else 0.0)
                 elif mode == "logdepth":
                     a = c0 if d == 1 else c0 * beta64 + math.log(float(d))
                 else:

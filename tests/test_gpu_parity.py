@@ -38,7 +38,7 @@ def test_score_tiny_trees_all_states(seed):
     assert none is None and np.array_equal(got_s2, got_s)
 
 
-@pytest.mark.parametrize("idx,mode", [(1, W_UNIFORM), (1, W_LOGDEPTH), (2, W_UNIFORM), (2, W_LOGDEPTH)])
+@pytest.mark.parametrize("idx,mode", [(1, W_UNIFORM), (1, W_LOGDEPTH), (2, W_UNIFORM), (2, W_LOGDEPTH), (2, 2)])
 def test_score_small_configs_all_or_many_states(idx, mode):
     cfg, toks, offs, ot, tr = config_trees(idx, mode)
     states = np.arange(min(ot.num_states, 3000), dtype=np.int32)

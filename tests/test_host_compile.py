@@ -76,7 +76,7 @@ def _rows_from_flat(h, V, blank, unk, s):
 
 
 @pytest.mark.parametrize("seed", range(30))
-@pytest.mark.parametrize("mode", [W_UNIFORM, W_LOGDEPTH])
+@pytest.mark.parametrize("mode", [W_UNIFORM, W_LOGDEPTH, 2])
 def test_tiny_trees_match_oracle(seed, mode):
     V = 5 + seed % 4
     blank = 0 if seed % 2 else -1

@@ -16,7 +16,9 @@ import pytest
 import pb_workloads as W
 from brute import BruteTree, kmp_automaton, topk_reference
 from oracle import OracleTree, OracleError
-from oracle.pb_oracle import W_LOGDEPTH, W_UNIFORM
+from oracle.pb_oracle import W_LOGDEPTH, W_UNIFORM, W_UNIFORM_FINAL
+
+WM = {"uniform": W_UNIFORM, "logdepth": W_LOGDEPTH, "uniform_final": W_UNIFORM_FINAL}
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -30,7 +32,8 @@ def _state_strings(tree: OracleTree):
 
 
 CASES = [(seed, mode, fzb, unk) for seed in range(60) for mode, fzb, unk in
-         [("uniform", True, 0.0), ("logdepth", True, 0.0), ("uniform", False, 0.0), ("logdepth", True, 0.75)]]
+         [("uniform", True, 0.0), ("logdepth", True, 0.0), ("uniform", False, 0.0), ("logdepth", True, 0.75),
+          ("uniform_final", True, 0.0), ("uniform_final", False, 0.5)]]
 
 
 @pytest.mark.parametrize("seed,mode,fzb,unk", CASES)
@@ -42,7 +45,7 @@ def test_oracle_matches_brute_force_all_pairs(seed, mode, fzb, unk):
     phrases = _phrases(toks, offs)
     bt = BruteTree(phrases, wts, mode=mode, beta=2.0, c_unk=unk, final_zero_backoff=fzb, blank=blank)
     ot = OracleTree(toks, offs, V, blank, weights=wts,
-                    weight_mode=W_UNIFORM if mode == "uniform" else W_LOGDEPTH, beta=2.0, unk_score=unk,
+                    weight_mode=WM[mode], beta=2.0, unk_score=unk,
                     final_zero_backoff=fzb)
     strings = _state_strings(ot)
     # the states are exactly the distinct phrase prefixes
@@ -81,7 +84,7 @@ def test_canonical_numbering_is_bfs_with_children_by_token():
 
 
 @pytest.mark.parametrize("seed", range(40))
-@pytest.mark.parametrize("mode", ["uniform", "logdepth"])
+@pytest.mark.parametrize("mode", ["uniform", "logdepth", "uniform_final"])
 def test_random_walk_history_state_and_telescoping(seed, mode):
     """Drive a long random token history through the oracle.
 
@@ -94,7 +97,7 @@ def test_random_walk_history_state_and_telescoping(seed, mode):
     V = 5
     toks, offs, wts = W.tiny_case(5000 + seed, vocab_size=V, blank_id=-1, max_phrases=8, max_len=6)
     phrases = _phrases(toks, offs)
-    wm = W_UNIFORM if mode == "uniform" else W_LOGDEPTH
+    wm = WM[mode]
     c_unk = 0.25
     plain = OracleTree(toks, offs, V, -1, weights=wts, weight_mode=wm, unk_score=0.0, final_zero_backoff=False)
     paper = OracleTree(toks, offs, V, -1, weights=wts, weight_mode=wm, unk_score=c_unk, final_zero_backoff=True)
@@ -416,3 +419,23 @@ def test_workload_generators_are_seeded_and_shaped():
     b = W.make_logp(cfg, chunk_frames=50)
     assert np.array_equal(a, b) and a.shape == (50, 4, 128) and a.dtype == np.float32
     assert np.allclose(np.exp(a.astype(np.float64)).sum(-1), 1.0, atol=1e-5)
+
+
+def test_uniform_weights_with_final_reward_by_hand():
+    """Phrases (1,2), (1,2,3) and (4,), every transition 1.0: the arc that completes a phrase also pays the
+    accumulated uniform score of the phrase (Sec. II-B, the uniform distribution with a final-node reward).
+
+      arc 1: 1          acc (1)     = 1
+      arc 2: 1 + 2 = 3  acc (1,2)   = 4      (two transitions completed)
+      arc 3: 1 + 3 = 4  acc (1,2,3) = 8      (three transitions completed)
+      arc 4: 1 + 1 = 2  acc (4)     = 2
+    """
+    ot = OracleTree(np.array([1, 2, 1, 2, 3, 4], np.int32), np.array([0, 2, 5, 6], np.int64), 6, 0,
+                    weight_mode=W_UNIFORM_FINAL)
+    by = {ot.prefix(s): ot.node(s) for s in range(ot.num_states)}
+    assert [by[k]["acc"] for k in [(1,), (1, 2), (1, 2, 3), (4,)]] == [1.0, 4.0, 8.0, 2.0]
+    assert [by[k]["arcw"] for k in [(1,), (1, 2), (1, 2, 3), (4,)]] == [1.0, 3.0, 4.0, 2.0]
+    s1 = [s for s in range(ot.num_states) if ot.prefix(s) == (1,)][0]
+    assert ot.query(s1, 5) == (-1.0, 0)          # partial match abandoned: its score is paid back
+    s12 = [s for s in range(ot.num_states) if ot.prefix(s) == (1, 2)][0]
+    assert ot.query(s12, 5) == (0.0, 0)          # a completed phrase keeps its score
