@@ -21,6 +21,9 @@
  *                              repeated V times; fusion is Eq. 1 evaluated per
  *                              token, followed by first-max argmax or by a full
  *                              sort of the beam*V candidates.
+ *   Sec. II-C                  the two-stage greedy token selection with the CTC rule for
+ *                              repeated labels, and the end-of-sentence heuristics of
+ *                              encoder-decoder models, each written out as the text states it.
  *
  * Arithmetic: tree scores are accumulated in double and rounded once to fp32;
  * query-time sums and the fusion run in fp32, one rounding per operation, no
