@@ -396,3 +396,64 @@ def test_fuse_exact_ties_between_arcs_in_different_lanes():
         torch.cuda.synchronize()
         assert np.array_equal(tk.cpu().numpy(), want[0]) and np.array_equal(st.cpu().numpy(), want[1])
         assert np.array_equal(sc.cpu().numpy(), want[2])
+
+
+def test_fuse_frames_config5_full_size():
+    """Large-vocabulary shape as written: V = 8192 (rows in eight chunks), blank-free, B = 256, 200 steps."""
+    cfg, toks, offs, ot, tr = config_trees(5)
+    logp = W.make_logp(cfg)
+    want = ot.fuse_frames(logp, np.zeros(cfg.batch, np.int32), cfg.alpha)
+    got = gpu_fuse_frames(tr, dev(logp), dev(np.zeros(cfg.batch, np.int32)), cfg.alpha)
+    assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1])
+    assert np.array_equal(got[2], want[2])
+
+
+def test_step_calls_replay_correctly_from_a_hip_graph():
+    """The step calls allocate nothing and synchronise nothing, so a decoding loop can be captured.  The
+    graph is replayed several times, with eager work and synchronisation in between and fresh inputs
+    copied into the captured buffers, and every replay is compared with the oracle."""
+    cfg, toks, offs, ot, tr = config_trees(2)
+    T, B, V = 24, cfg.batch, cfg.vocab_size
+    U, K = B // 4, 4
+    d_logp = torch.zeros((T, B, V), dtype=torch.float32, device=DEV)
+    d_s0 = torch.zeros(B, dtype=torch.int32, device=DEV)
+    d_tok = torch.zeros((T, B), dtype=torch.int32, device=DEV)
+    d_st = torch.zeros((T, B), dtype=torch.int32, device=DEV)
+    d_sc = torch.zeros((T, B), dtype=torch.float32, device=DEV)
+    f_tok, f_st, f_sc = torch.zeros_like(d_tok), torch.zeros_like(d_st), torch.zeros_like(d_sc)
+    d_hyp = torch.zeros(B, dtype=torch.float32, device=DEV)
+    beam = [torch.zeros(B, dtype=torch.int32, device=DEV) for _ in range(3)] + [torch.zeros(B, device=DEV)]
+    d_rows = torch.zeros((B, V), dtype=torch.float32, device=DEV)
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            sp = int(side.cuda_stream)
+            prev = d_s0
+            for t in range(T):
+                pb.pb_fuse_step_select(tr, d_logp[t], V, prev, d_tok[t - 1] if t else None, cfg.alpha, B,
+                                       pb.PB_SELECT_TWO_STAGE_CTC, d_tok[t], d_st[t], d_sc[t], sp)
+                prev = d_st[t]
+            pb.pb_fuse_frames(tr, d_logp, B * V, V, d_s0, cfg.alpha, T, B, f_tok, f_st, f_sc, sp)
+            pb.pb_fuse_step_beam(tr, d_logp[0], V, d_hyp, d_s0, cfg.alpha, U, K, beam[0], beam[1], beam[2], beam[3], sp)
+            pb.pb_score(tr, d_st[T - 1], B, d_rows, None, sp)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        logp = W.sticky_logp(50 + rep, T, B, V, cfg.blank_id, grid=None, bump=10.0)
+        s0 = W.sample_states(ot.num_states, B, 60 + rep)
+        hyp = np.random.default_rng(rep).standard_normal(B).astype(np.float32)
+        d_logp.copy_(dev(logp)); d_s0.copy_(dev(s0)); d_hyp.copy_(dev(hyp))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        want = ot.fuse_frames_select(logp, s0, None, cfg.alpha, 2)
+        assert np.array_equal(d_tok.cpu().numpy(), want[0]) and np.array_equal(d_st.cpu().numpy(), want[1])
+        assert_scores(d_sc.cpu().numpy(), want[2])
+        wf = ot.fuse_frames(logp, s0, cfg.alpha)
+        assert np.array_equal(f_tok.cpu().numpy(), wf[0]) and np.array_equal(f_st.cpu().numpy(), wf[1])
+        wb = ot.fuse_step_beam(logp[0], hyp, s0, cfg.alpha, U, K)
+        for got, w in zip(beam[:3], wb[:3]):
+            assert np.array_equal(got.cpu().numpy(), w)
+        assert_scores(d_rows.cpu().numpy(), ot.score(want[1][T - 1])[0])
+        (d_rows * 2).sum().item()      # eager work between the replays
