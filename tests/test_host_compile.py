@@ -195,3 +195,21 @@ def test_eos_options_are_validated_and_reported():
     tr = pb.pb_build(toks, offs, 6, 0, device=-1, eos_id=5, final_eos_score=2.0)
     assert pb.pb_info(tr)["eos_id"] == 5
     assert pb.pb_info(pb.pb_build(toks, offs, 6, 0, device=-1))["eos_id"] == -1
+
+
+def test_host_compiler_is_clean_under_address_and_ub_sanitizers(tmp_path):
+    """tests/host_compile_sanitized.cpp: the compiler alone (no HIP runtime) built with g++ -fsanitize."""
+    import shutil
+    import subprocess
+    if shutil.which("g++") is None:
+        pytest.skip("no g++")
+    exe = str(tmp_path / "host_compile_sanitized")
+    csrc = os.path.join(ROOT, "paper_2508_07014_amd", "csrc")
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+           "-static-libasan", "-static-libubsan",
+           "-I", os.path.join(ROOT, "include"), "-I", csrc, os.path.join(ROOT, "tests", "host_compile_sanitized.cpp"),
+           os.path.join(csrc, "pb_compile.cpp"), "-o", exe]
+    subprocess.run(cmd, check=True)
+    run = subprocess.run([exe], capture_output=True, text=True)
+    assert run.returncode == 0, run.stdout + run.stderr
+    assert "clean" in run.stdout
