@@ -786,8 +786,8 @@ __global__ void __launch_bounds__(256, 4) frames_spec_kernel(DeviceTree dt, cons
 // Pass 2: one workgroup per hypothesis; its waves share the segments j = 1 .. nseg-1.
 //   (a) segment j is re-run from the outcome pass 1 left at the end of segment j-1 (end state and,
 //       under the CTC rule, last label) until the stored trajectory is met;
-//   (b) wave 0 then compares, for all segments at once, the outcome at the end of segment j-1 with
-//       the one segment j was re-run from, and repairs mismatches in order the same way.
+//   (b) the outcome at the end of segment j-1 is then compared, for all segments at once, with the
+//       one segment j was re-run from, and the stale segments are re-run, in parallel rounds.
 template <int MODE, int SEL>
 __global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, const float* __restrict__ logp,
                                                           int64_t frame_stride, int64_t row_stride, float alpha, int T,
@@ -795,6 +795,7 @@ __global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, const f
                                                           int32_t* __restrict__ states, float* __restrict__ scores) {
   extern __shared__ float lds[];
   __shared__ int assumed[64], assumed_tok[64];
+  __shared__ unsigned bad_lo, bad_hi;
   const int lane = threadIdx.x & 63, wave = uniform_i(threadIdx.x >> 6), nwaves = blockDim.x >> 6;
   const int b = blockIdx.x;
   float* row = lds + wave * kWaveLdsFloats;
@@ -823,27 +824,35 @@ __global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, const f
     }
     rerun(seg, s, last);  // pass 1 assumed the root: a segment whose neighbour ended there meets at once
   }
-  __threadfence_block();
-  __syncthreads();
-  if (wave == 0) {
-    u64 done = 1;  // segment 0 is exact
-    for (;;) {
+  // (b) rounds: wave 0 compares the outcome at the end of every segment j-1 with what segment j was last
+  // re-run from and publishes the set of stale segments; the waves re-run those in parallel from the
+  // current outcomes.  Segment 0 is exact, so after round r the segments up to r + 1 are final: at most
+  // nseg rounds, in practice one or two.
+  for (;;) {
+    __threadfence_block();
+    __syncthreads();
+    if (wave == 0) {
       const bool check = lane >= 1 && lane < nseg;
       const int have = check ? end_state_of(lane - 1) : 0;
       const int have_tok = check ? end_token_of(lane - 1) : 0;
-      const int want = check ? assumed[lane] : 0;
-      const int want_tok = check ? assumed_tok[lane] : 0;
-      const u64 bad = __ballot(check && (have != want || (SEL == 2 && have_tok != want_tok))) & ~done;
-      if (bad == 0) break;
-      const int seg = first_lane(bad);
-      const int s = __builtin_amdgcn_readlane(have, seg);
-      const int last = __builtin_amdgcn_readlane(have_tok, seg);
-      if (lane == 0) {
-        assumed[seg] = s;
-        assumed_tok[seg] = last;
+      const bool stale = check && (have != assumed[lane] || (SEL == 2 && have_tok != assumed_tok[lane]));
+      if (stale) {
+        assumed[lane] = have;
+        assumed_tok[lane] = have_tok;
       }
-      rerun(seg, s, last);
-      done |= (2ull << seg) - 1;  // segments up to `seg` are final now
+      const u64 bad = __ballot(stale);
+      if (lane == 0) {
+        bad_lo = static_cast<unsigned>(bad);
+        bad_hi = static_cast<unsigned>(bad >> 32);
+      }
+    }
+    __syncthreads();
+    u64 bad = (static_cast<u64>(bad_hi) << 32) | bad_lo;
+    if (bad == 0) break;
+    for (int k = 0; bad != 0; ++k) {  // the k-th stale segment goes to wave k mod nwaves
+      const int seg = first_lane(bad);
+      bad &= bad - 1;
+      if (k % nwaves == wave) rerun(seg, assumed[seg], assumed_tok[seg]);
     }
   }
 }
