@@ -457,3 +457,21 @@ def test_step_calls_replay_correctly_from_a_hip_graph():
             assert np.array_equal(got.cpu().numpy(), w)
         assert_scores(d_rows.cpu().numpy(), ot.score(want[1][T - 1])[0])
         (d_rows * 2).sum().item()      # eager work between the replays
+
+
+@pytest.mark.parametrize("T,B", [(1, 1), (2, 1), (3000, 2), (700, 1), (65, 130)])
+def test_fuse_frames_extreme_shapes(T, B):
+    """One frame, one hypothesis, segments longer than 64 frames, more hypotheses than chains per segment."""
+    cfg, toks, offs, ot, tr = config_trees(2)
+    logp = W.make_logp(cfg, steps=T, batch=B, planting=W.Planting(toks, offs, cover=0.5))
+    s0 = W.sample_states(ot.num_states, B, T + B)
+    for mode in (0, 2):
+        want = ot.fuse_frames_select(logp, s0, None, cfg.alpha, mode)
+        d_tok = torch.full((T, B), -5, dtype=torch.int32, device=DEV)
+        d_st = torch.full((T, B), -5, dtype=torch.int32, device=DEV)
+        d_sc = torch.zeros((T, B), dtype=torch.float32, device=DEV)
+        pb.pb_fuse_frames_select(tr, dev(logp), B * cfg.vocab_size, cfg.vocab_size, dev(s0), None, cfg.alpha, T, B, mode,
+                                 d_tok, d_st, d_sc, stream_ptr())
+        torch.cuda.synchronize()
+        assert np.array_equal(d_tok.cpu().numpy(), want[0]) and np.array_equal(d_st.cpu().numpy(), want[1])
+        assert_scores(d_sc.cpu().numpy(), want[2])
