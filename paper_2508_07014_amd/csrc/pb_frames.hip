@@ -1,10 +1,13 @@
-// Wave-per-hypothesis greedy kernels (gfx950, wave64): the fused step and the multi-frame decoder.
+// Wave-per-hypothesis kernels (gfx950, wave64): the fused greedy step with its selection rules, the
+// multi-frame decoder and the beam step for rows of up to 1024 tokens.
 //
 // One wavefront owns one hypothesis row; nothing crosses waves, so there is no barrier on the path.
 //
 //  * Row streaming.  A row is consumed in chunks of 1024 tokens; lane l owns tokens
 //    256*i + 4*l + {0..3}, i = 0..3 of a chunk, so each of the four 16-byte loads of a lane is part
-//    of one contiguous 1 KiB wave access.  The next row is requested before the current one is used.
+//    of one contiguous 1 KiB wave access.  Rows travel through a ring of register buffers, requested
+//    one or two frames ahead.  Vector loads retire in order, so the first 64 arcs of the state are
+//    requested before the row prefetch of the frame: a wait for them then leaves the prefetch in flight.
 //  * Base candidates.  For every token that no chain state overrides the boost is
 //    p_root + root_score[v] (all backoffs down to the root, then the root arc or the c_unk
 //    self-loop).  alpha * that is cached per lane while p_root does not change, so the common
@@ -24,9 +27,13 @@
 //    every segment but the first speculatively from the root state.  The decoder is a finite
 //    automaton step, so a re-run from the true start state needs to go only as far as the frame
 //    where its state meets the speculative trajectory; a second kernel does these short re-runs
-//    (all segments in parallel, from the neighbouring segment's end state) and then validates the
-//    assumed start states in order, repairing where a re-run changed a segment's end state.
+//    (all segments in parallel, from the neighbouring segment's end state) and then compares the
+//    assumed start states with the final ones, re-running the stale segments in parallel rounds.
 //    The result is identical to T sequential steps.
+//  * Selection rules (Sec. II-C).  The two-stage rules first take the arg-max of the raw row; a blank
+//    (or, for CTC, a repeat of the previous label) ends the frame there.  Tokens barred from the
+//    boosted re-selection are NaN in the candidate registers, which no maximum and no equality test
+//    ever selects.
 #include <hip/hip_runtime.h>
 
 #include <climits>
