@@ -269,7 +269,7 @@ def main() -> int:
         tree5 = pb.pb_build(t5, o5, cfg5.vocab_size, cfg5.blank_id, device=0)
         n5 = pb.pb_info(tree5)["num_states"]
         sweep = {}
-        for Bs in (64, 256, 1024):
+        for Bs in (64, 256, 1024, 4096):
             st = torch.from_numpy(W.sample_states(n5, Bs, 100 + Bs)).to(dev)
             sc = torch.empty((Bs, cfg5.vocab_size), dtype=torch.float32, device=dev)
             nx = torch.empty((Bs, cfg5.vocab_size), dtype=torch.int32, device=dev)

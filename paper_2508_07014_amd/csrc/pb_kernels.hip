@@ -137,49 +137,80 @@ __global__ void __launch_bounds__(256) score_eos_kernel(DeviceTree t, const int3
 }
 
 // ------------------------------------------------------------------------------------------------
-// pb_score: one workgroup per (hypothesis, vocabulary tile).
+// pb_score: one workgroup per (group of `per` consecutive hypotheses, vocabulary tile).  The tile of
+// the dense root row is read once per workgroup and kept in registers (VEC == 4: up to 8 tokens per
+// thread).  A hypothesis in the root state has no chain: its row is
+// the root row itself and skips LDS and barriers.
 template <int VEC>
-__global__ void __launch_bounds__(256) score_kernel(DeviceTree t, const int32_t* __restrict__ states,
+__global__ void __launch_bounds__(256) score_kernel(DeviceTree t, const int32_t* __restrict__ states, int B,
                                                     float* __restrict__ scores, int32_t* __restrict__ next,
-                                                    int tile, int tiles) {
+                                                    int tile, int tiles, int per) {
   extern __shared__ u64 row[];
-  const int b = blockIdx.x / tiles;
-  const int v0 = (blockIdx.x - b * tiles) * tile;
+  const int grp = blockIdx.x / tiles;
+  const int v0 = (blockIdx.x - grp * tiles) * tile;
   const int V = t.vocab_size;
   const int n = min(tile, V - v0);
-  const int s = states[b];
-  const size_t base = static_cast<size_t>(b) * V + v0;
-  if (static_cast<unsigned>(s) >= static_cast<unsigned>(t.num_states)) {
-    for (int i = threadIdx.x; i < n; i += blockDim.x) {
-      scores[base + i] = NAN;
-      if (next) next[base + i] = -1;
-    }
-    return;
-  }
-  for (int i = threadIdx.x; i < n; i += blockDim.x) row[i] = 0ull;
-  __syncthreads();
-  const float p_root = scatter_chain(t, s, v0, n, row);
-  __syncthreads();
+  constexpr int kMaxSlots = kScoreTile / (256 * 4);  // float4 groups per thread
+  float4 rs[kMaxSlots];
+  int4 rn[kMaxSlots];
   if constexpr (VEC == 4) {
-    for (int i = threadIdx.x * 4; i < n; i += blockDim.x * 4) {
-      const float4 rs = *reinterpret_cast<const float4*>(t.root_score + v0 + i);
-      const int4 rn = *reinterpret_cast<const int4*>(t.root_next + v0 + i);
-      const float rsa[4] = {rs.x, rs.y, rs.z, rs.w};
-      const int rna[4] = {rn.x, rn.y, rn.z, rn.w};
-      float sc[4];
-      int nx[4];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) resolve(t, s, p_root, row[i + k], v0 + i + k, rsa[k], rna[k], sc[k], nx[k]);
-      *reinterpret_cast<float4*>(scores + base + i) = make_float4(sc[0], sc[1], sc[2], sc[3]);
-      if (next) *reinterpret_cast<int4*>(next + base + i) = make_int4(nx[0], nx[1], nx[2], nx[3]);
+    for (int q = 0; q < kMaxSlots; ++q) {
+      const int i = (q * 256 + static_cast<int>(threadIdx.x)) * 4;
+      if (i < n) {
+        rs[q] = *reinterpret_cast<const float4*>(t.root_score + v0 + i);
+        rn[q] = *reinterpret_cast<const int4*>(t.root_next + v0 + i);
+      }
     }
-  } else {
-    for (int i = threadIdx.x; i < n; i += blockDim.x) {
-      float sc;
-      int nx;
-      resolve(t, s, p_root, row[i], v0 + i, t.root_score[v0 + i], t.root_next[v0 + i], sc, nx);
-      scores[base + i] = sc;
-      if (next) next[base + i] = nx;
+  }
+  const int b_end = min(B, (grp + 1) * per);
+  for (int b = grp * per; b < b_end; ++b) {
+    const int s = states[b];
+    const size_t base = static_cast<size_t>(b) * V + v0;
+    if (static_cast<unsigned>(s) >= static_cast<unsigned>(t.num_states)) {
+      for (int i = threadIdx.x; i < n; i += blockDim.x) {
+        scores[base + i] = NAN;
+        if (next) next[base + i] = -1;
+      }
+      continue;
+    }
+    const bool chain = s != 0;  // uniform over the workgroup
+    float p_root = 0.0f;
+    if (chain) {
+      __syncthreads();  // everyone has read the previous hypothesis' entries
+      for (int i = threadIdx.x; i < n; i += blockDim.x) row[i] = 0ull;
+      __syncthreads();
+      p_root = scatter_chain(t, s, v0, n, row);
+      __syncthreads();
+    }
+    if constexpr (VEC == 4) {
+#pragma unroll
+      for (int q = 0; q < kMaxSlots; ++q) {
+        const int i = (q * 256 + static_cast<int>(threadIdx.x)) * 4;
+        if (i < n) {
+          const float rsa[4] = {rs[q].x, rs[q].y, rs[q].z, rs[q].w};
+          const int rna[4] = {rn[q].x, rn[q].y, rn[q].z, rn[q].w};
+          float sc[4];
+          int nx[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k)
+            resolve(t, s, p_root, chain ? row[i + k] : 0ull, v0 + i + k, rsa[k], rna[k], sc[k], nx[k]);
+          typedef float vf4 __attribute__((ext_vector_type(4)));
+          typedef int vi4 __attribute__((ext_vector_type(4)));
+          const vf4 so = {sc[0], sc[1], sc[2], sc[3]};
+          const vi4 no = {nx[0], nx[1], nx[2], nx[3]};
+          *reinterpret_cast<vf4*>(scores + base + i) = so;
+          if (next) *reinterpret_cast<vi4*>(next + base + i) = no;
+        }
+      }
+    } else {
+      for (int i = threadIdx.x; i < n; i += blockDim.x) {
+        float sc;
+        int nx;
+        resolve(t, s, p_root, chain ? row[i] : 0ull, v0 + i, t.root_score[v0 + i], t.root_next[v0 + i], sc, nx);
+        scores[base + i] = sc;
+        if (next) next[base + i] = nx;
+      }
     }
   }
 }
@@ -510,14 +541,20 @@ int launch_score(const DeviceTree& t, const int32_t* d_states, int32_t B, float*
   const int V = t.vocab_size;
   const int tile = V < kScoreTile ? ((V + 3) & ~3) : kScoreTile;
   const int tiles = (V + tile - 1) / tile;
-  if (static_cast<int64_t>(B) * tiles > INT32_MAX) return PB_EUNSUPPORTED;
-  const dim3 grid(static_cast<unsigned>(B * tiles));
+  // hypotheses per workgroup: one while the launch is small, up to four once 4096 workgroups remain
+  const int64_t wgs = static_cast<int64_t>(B) * tiles;
+  const int per = wgs >= 4 * 4096 ? 4 : (wgs >= 2 * 4096 ? 2 : 1);
+  const int64_t groups = (static_cast<int64_t>(B) + per - 1) / per;
+  if (groups * tiles > INT32_MAX) return PB_EUNSUPPORTED;
+  const dim3 grid(static_cast<unsigned>(groups * tiles));
   const size_t lds = static_cast<size_t>(tile) * sizeof(u64);
   const bool vec = (V % 4 == 0) && aligned16(d_scores) && (d_next == nullptr || aligned16(d_next));
   if (vec)
-    hipLaunchKernelGGL(score_kernel<4>, grid, dim3(256), lds, stream, t, d_states, d_scores, d_next, tile, tiles);
+    hipLaunchKernelGGL(score_kernel<4>, grid, dim3(256), lds, stream, t, d_states, B, d_scores, d_next, tile, tiles,
+                       per);
   else
-    hipLaunchKernelGGL(score_kernel<1>, grid, dim3(256), lds, stream, t, d_states, d_scores, d_next, tile, tiles);
+    hipLaunchKernelGGL(score_kernel<1>, grid, dim3(256), lds, stream, t, d_states, B, d_scores, d_next, tile, tiles,
+                       per);
   if (t.eos_id >= 0)
     hipLaunchKernelGGL(score_eos_kernel, dim3(static_cast<unsigned>(B)), dim3(256), 0, stream, t, d_states, d_scores,
                        d_next);
