@@ -19,7 +19,10 @@ int launch_fuse(const DeviceTree& t, const float* d_logp, int64_t frame_stride, 
                 int32_t* d_tokens, int32_t* d_states, float* d_scores, hipStream_t stream);
 
 // Wave-per-hypothesis greedy kernels (pb_frames.hip); usable when rows are 16-byte aligned and V % 4 == 0.
-constexpr int kTargetChains = 4096;  // concurrent decode chains aimed for by the multi-frame decoder
+#ifndef PB_TARGET_CHAINS
+#define PB_TARGET_CHAINS 4096
+#endif
+constexpr int kTargetChains = PB_TARGET_CHAINS;  // concurrent decode chains aimed for by the multi-frame decoder
 constexpr int kMinSegLen = 8;        // shortest speculative segment, in frames
 constexpr int kMaxSegments = 64;     // segments per hypothesis (one lane each in the validation pass)
 
