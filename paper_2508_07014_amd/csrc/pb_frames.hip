@@ -276,10 +276,11 @@ __device__ __forceinline__ void rebuild_base_boost(const TreeView& t, int lane, 
 //   c / c_p  cached base boosts and the p_root they are for
 //   row / tags  this wave's LDS copy of the row and its token marks
 //   last  label of the previous frame (SEL == 2 only; any value outside [0, V) = none)
+//   need_record  false when no frame follows: the record of the next state is then not fetched
 template <bool FULL, int SEL, typename NextRow>
 __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const float (&x)[16], float (&c)[16],
                                          float& c_p, float alpha, float* row, unsigned* tags, int lane, int last,
-                                         NextRow&& next_row, float& out_val, int& out_tok) {
+                                         bool need_record, NextRow&& next_row, float& out_val, int& out_tok) {
   const int s = cur.s;
   const Rec rec0 = cur.rec;
   const bool chain = (s != 0);
@@ -426,7 +427,11 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
     if (arc_wins) {
       out_val = MA;
       out_tok = va;
-      cur = cursor_at(t, achild);
+      if (need_record) {
+        cur = cursor_at(t, achild);
+      } else {  // last frame of the call: only the state id leaves the kernel
+        cur.s = achild;
+      }
     } else {
       out_val = base_val;
       out_tok = base_tok;
@@ -482,6 +487,7 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
   float xb[NB][16], c[16];
   load16<FULL>(rp, 0, V, lane, -INFINITY, xb[0]);
   if (NB == 3 && f0 + 1 < f1) load16<FULL>(rp + frame_stride, 0, V, lane, -INFINITY, xb[1]);
+  load16<FULL>(t.root_score, 0, V, lane, 0.0f, c);  // needs no state: requested before the state is looked at
   const int s = uniform_i(s_in);
   int last = -1;
   if (SEL == 2) last = uniform_i(last_in);
@@ -491,7 +497,7 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
   }
   Cursor cur = cursor_at(t, s);
   float c_p = cur.p_root;
-  rebuild_base_boost<FULL, SEL>(t, lane, c_p, alpha, c);
+  make_base_boost<SEL>(0, lane, t.blank, c_p, alpha, c, c);  // element-wise, in place
   // Outputs.  The single-stage decode keeps those of up to 64 consecutive frames in the lanes (frame
   // base + l in lane l) and writes them together, so that no store sits in the in-order queue of the
   // loads; a re-run writes frame by frame, right after it has compared with what is stored, and so do
@@ -518,7 +524,7 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
         const float* rpn = rp + (NB - 1) * frame_stride;
         float val;
         int tok;
-        frame_1k<FULL, SEL>(t, cur, xb[u], c, c_p, alpha, row, tags, lane, last,
+        frame_1k<FULL, SEL>(t, cur, xb[u], c, c_p, alpha, row, tags, lane, last, f + 1 < f1,
                             [&]() { if (more) load16<FULL>(rpn, 0, V, lane, -INFINITY, xb[(u + NB - 1) % NB]); }, val,
                             tok);
         if (!DEFER) {
