@@ -261,6 +261,18 @@ def main() -> int:
             ms = _events(torch, g.replay, 5)
             extra["graph_replay"] = {"us_per_frame": ms * 1e3 / frames, "hyp_frames_per_s": B * frames / (ms * 1e-3),
                                      "GBps": frames * B * (4 * V + 12) / (ms * 1e-3) / 1e9}
+            # the floor of that regime: the same number of dependent, nearly empty kernels in a graph
+            g0 = torch.cuda.CUDAGraph()
+            side.wait_stream(torch.cuda.current_stream())
+            tiny = torch.zeros(4, dtype=torch.int32, device=dev)
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(g0, stream=side):
+                    for t in range(frames):
+                        pb.pb_diag_chase(tiny, 4, 0, 0, d_one, int(side.cuda_stream))
+            torch.cuda.current_stream().wait_stream(side)
+            g0.replay()
+            torch.cuda.synchronize()
+            extra["graph_replay"]["empty_kernel_us_per_node"] = _events(torch, g0.replay, 5) * 1e3 / frames
         except Exception as e:  # the graph regime is a side measurement; say why it is missing
             extra["graph_replay"] = {"error": repr(e)}
         # dense rows: config 5 sweep (V = 8192, 20K phrases), states drawn from all states
