@@ -213,6 +213,29 @@ int pb_fuse_step_beam(const pb_tree* tree, const float* d_logp, int64_t row_stri
                       int32_t* d_parents, int32_t* d_states_out, float* d_scores_out, void* hip_stream);
 
 /*
+ * Forests -- a different context list per hypothesis (or, in the beam step, per utterance).  Not in the
+ * paper, whose decoders use one list per run; serving needs one per request.
+ *   pb_forest_build groups n_trees trees built for the same device with the same vocab_size and blank_id
+ *   and without an EOS rule (PB_EUNSUPPORTED otherwise; PB_EINVAL for null arguments, n_trees < 1 or a
+ *   host-only tree).  The forest refers to the trees' device arrays: free it before them.
+ *   The *_forest calls are pb_score, pb_fuse_step_select and pb_fuse_step_beam with one more device
+ *   array: d_tree_ids int32[B] (beam: int32[U]) names the member tree of every row; states are states
+ *   of that tree.  An id outside [0, n_trees) marks the row's outputs like an invalid state (-1 / NaN).
+ */
+typedef struct pb_forest pb_forest;
+int pb_forest_build(const pb_tree* const* trees, int32_t n_trees, pb_forest** out);
+int pb_forest_free(pb_forest* forest);
+int pb_score_forest(const pb_forest* forest, const int32_t* d_tree_ids, const int32_t* d_states, int32_t B,
+                    float* d_scores, int32_t* d_next, void* hip_stream);
+int pb_fuse_step_forest(const pb_forest* forest, const float* d_logp, int64_t row_stride, const int32_t* d_tree_ids,
+                        const int32_t* d_states_in, const int32_t* d_last_tokens, float alpha, int32_t B, int32_t mode,
+                        int32_t* d_tokens, int32_t* d_states_out, float* d_scores, void* hip_stream);
+int pb_fuse_step_beam_forest(const pb_forest* forest, const float* d_logp, int64_t row_stride,
+                             const int32_t* d_tree_ids, const float* d_hyp_scores, const int32_t* d_states_in,
+                             float alpha, int32_t U, int32_t K, int32_t* d_tokens, int32_t* d_parents,
+                             int32_t* d_states_out, float* d_scores_out, void* hip_stream);
+
+/*
  * pb_diag_chase -- measurement aid, not part of the method: one GPU lane performs `hops` dependent
  * loads i = d_table[i] starting at i = start and writes the last index to *d_out.  Timed by the
  * caller (events on the stream), it gives the latency of one dependent access for a table of n

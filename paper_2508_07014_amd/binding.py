@@ -18,7 +18,8 @@ PB_W_UNIFORM, PB_W_LOGDEPTH, PB_W_UNIFORM_FINAL = 0, 1, 2
 PB_SELECT_FUSED, PB_SELECT_TWO_STAGE, PB_SELECT_TWO_STAGE_CTC = 0, 1, 2
 
 EXPORTS = ["pb_build", "pb_free", "pb_info", "pb_host_arrays", "pb_state_prefix", "pb_score", "pb_fuse_step",
-           "pb_fuse_frames", "pb_fuse_step_select", "pb_fuse_frames_select", "pb_fuse_step_beam", "pb_diag_chase", "pb_strerror"]
+           "pb_fuse_frames", "pb_fuse_step_select", "pb_fuse_frames_select", "pb_fuse_step_beam", "pb_diag_chase", "pb_forest_build", "pb_forest_free", "pb_score_forest",
+           "pb_fuse_step_forest", "pb_fuse_step_beam_forest", "pb_strerror"]
 
 
 class PbError(RuntimeError):
@@ -93,6 +94,17 @@ def load():
     lib.pb_fuse_step_beam.argtypes = [vp, vp, C.c_int64, vp, vp, C.c_float, C.c_int32, C.c_int32, vp, vp, vp, vp, vp]
     lib.pb_diag_chase.restype = C.c_int
     lib.pb_diag_chase.argtypes = [vp, C.c_int64, C.c_int32, C.c_int32, vp, vp]
+    lib.pb_forest_build.restype = C.c_int
+    lib.pb_forest_build.argtypes = [C.POINTER(vp), C.c_int32, C.POINTER(vp)]
+    lib.pb_forest_free.restype = C.c_int
+    lib.pb_forest_free.argtypes = [vp]
+    lib.pb_score_forest.restype = C.c_int
+    lib.pb_score_forest.argtypes = [vp, vp, vp, C.c_int32, vp, vp, vp]
+    lib.pb_fuse_step_forest.restype = C.c_int
+    lib.pb_fuse_step_forest.argtypes = [vp, vp, C.c_int64, vp, vp, vp, C.c_float, C.c_int32, C.c_int32, vp, vp, vp, vp]
+    lib.pb_fuse_step_beam_forest.restype = C.c_int
+    lib.pb_fuse_step_beam_forest.argtypes = [vp, vp, C.c_int64, vp, vp, vp, C.c_float, C.c_int32, C.c_int32, vp, vp, vp,
+                                             vp, vp]
     lib.pb_strerror.restype = C.c_char_p
     lib.pb_strerror.argtypes = [C.c_int]
     _lib = lib
@@ -227,3 +239,54 @@ def pb_fuse_step_beam(tree: Tree, d_logp, row_stride: int, d_hyp_scores, d_state
 
 def pb_diag_chase(d_table, n: int, start: int, hops: int, d_out, stream: int = 0):
     _check(load().pb_diag_chase(_dptr(d_table), n, start, hops, _dptr(d_out), stream or None), "pb_diag_chase")
+
+
+class Forest:
+    """Owner of a ``pb_forest*``; keeps its member trees alive."""
+
+    def __init__(self, handle: int, trees):
+        self.handle = handle
+        self.trees = list(trees)
+
+    def close(self):
+        if self.handle:
+            load().pb_forest_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def pb_forest_build(trees) -> Forest:
+    arr = (C.c_void_p * len(trees))(*[t.handle for t in trees])
+    out = C.c_void_p()
+    _check(load().pb_forest_build(arr, len(trees), C.byref(out)), "pb_forest_build")
+    return Forest(out.value, trees)
+
+
+def pb_forest_free(forest: Forest):
+    forest.close()
+
+
+def pb_score_forest(forest: Forest, d_tree_ids, d_states, B: int, d_scores, d_next=None, stream: int = 0):
+    _check(load().pb_score_forest(forest.handle, _dptr(d_tree_ids), _dptr(d_states), B, _dptr(d_scores), _dptr(d_next),
+                                  stream or None), "pb_score_forest")
+
+
+def pb_fuse_step_forest(forest: Forest, d_logp, row_stride: int, d_tree_ids, d_states_in, d_last_tokens, alpha: float,
+                        B: int, mode: int, d_tokens, d_states_out, d_scores, stream: int = 0):
+    _check(load().pb_fuse_step_forest(forest.handle, _dptr(d_logp), row_stride, _dptr(d_tree_ids), _dptr(d_states_in),
+                                      _dptr(d_last_tokens), alpha, B, mode, _dptr(d_tokens), _dptr(d_states_out),
+                                      _dptr(d_scores), stream or None), "pb_fuse_step_forest")
+
+
+def pb_fuse_step_beam_forest(forest: Forest, d_logp, row_stride: int, d_tree_ids, d_hyp_scores, d_states_in,
+                             alpha: float, U: int, K: int, d_tokens, d_parents, d_states_out, d_scores_out,
+                             stream: int = 0):
+    _check(load().pb_fuse_step_beam_forest(forest.handle, _dptr(d_logp), row_stride, _dptr(d_tree_ids),
+                                           _dptr(d_hyp_scores), _dptr(d_states_in), alpha, U, K, _dptr(d_tokens),
+                                           _dptr(d_parents), _dptr(d_states_out), _dptr(d_scores_out), stream or None),
+           "pb_fuse_step_beam_forest")

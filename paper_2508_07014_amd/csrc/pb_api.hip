@@ -5,6 +5,7 @@
 #include <climits>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "pb.h"
 #include "pb_kernels.hpp"
@@ -159,7 +160,8 @@ int pb_score(const pb_tree* tree, const int32_t* d_states, int32_t B, float* d_s
   if (!on_device(tree) || B < 0) return PB_EINVAL;
   if (B == 0) return PB_OK;
   if (!d_states || !d_scores) return PB_EINVAL;
-  return pb::launch_score(tree->dev, d_states, B, d_scores, d_next, static_cast<hipStream_t>(hip_stream));
+  return pb::launch_score(tree->dev, pb::TreePick{}, d_states, B, d_scores, d_next,
+                          static_cast<hipStream_t>(hip_stream));
 }
 
 int pb_fuse_step_select(const pb_tree* tree, const float* d_logp, int64_t row_stride, const int32_t* d_states_in,
@@ -172,9 +174,9 @@ int pb_fuse_step_select(const pb_tree* tree, const float* d_logp, int64_t row_st
   if (row_stride < tree->dev.vocab_size) return PB_EINVAL;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (pb::wave_path_ok(tree->dev, d_logp, 0, row_stride))
-    return pb::launch_step_wave(tree->dev, d_logp, row_stride, d_states_in, d_last_tokens, alpha, B, mode, d_tokens,
+    return pb::launch_step_wave(tree->dev, pb::TreePick{}, d_logp, row_stride, d_states_in, d_last_tokens, alpha, B, mode, d_tokens,
                                 d_states_out, d_scores, stream);
-  return pb::launch_fuse(tree->dev, d_logp, 0, row_stride, d_states_in, d_last_tokens, alpha, 1, B, mode, d_tokens,
+  return pb::launch_fuse(tree->dev, pb::TreePick{}, d_logp, 0, row_stride, d_states_in, d_last_tokens, alpha, 1, B, mode, d_tokens,
                          d_states_out, d_scores, stream);
 }
 
@@ -197,7 +199,7 @@ int pb_fuse_frames_select(const pb_tree* tree, const float* d_logp, int64_t fram
   if (pb::wave_path_ok(tree->dev, d_logp, frame_stride, row_stride))
     return pb::launch_frames_wave(tree->dev, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, mode,
                                   d_tokens, d_states, d_scores, stream);
-  return pb::launch_fuse(tree->dev, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, mode, d_tokens,
+  return pb::launch_fuse(tree->dev, pb::TreePick{}, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, mode, d_tokens,
                          d_states, d_scores, stream);
 }
 
@@ -224,8 +226,108 @@ int pb_fuse_step_beam(const pb_tree* tree, const float* d_logp, int64_t row_stri
   if (pb::beam_wave_ok(tree->dev, d_logp, row_stride, K))
     return pb::launch_beam_wave(tree->dev, d_logp, row_stride, d_hyp_scores, d_states_in, alpha, U, K, d_tokens,
                                 d_parents, d_states_out, d_scores_out, static_cast<hipStream_t>(hip_stream));
-  return pb::launch_beam(tree->dev, d_logp, row_stride, d_hyp_scores, d_states_in, alpha, U, K, d_tokens, d_parents,
+  return pb::launch_beam(tree->dev, pb::TreePick{}, d_logp, row_stride, d_hyp_scores, d_states_in, alpha, U, K, d_tokens, d_parents,
                          d_states_out, d_scores_out, static_cast<hipStream_t>(hip_stream));
+}
+
+int pb_forest_build(const pb_tree* const* trees, int32_t n_trees, pb_forest** out) {
+  if (!trees || !out || n_trees < 1) return PB_EINVAL;
+  for (int32_t i = 0; i < n_trees; ++i)
+    if (!on_device(trees[i])) return PB_EINVAL;
+  const pb_tree* first = trees[0];
+  std::vector<pb::DeviceTree> table(static_cast<size_t>(n_trees));
+  for (int32_t i = 0; i < n_trees; ++i) {
+    const pb_tree* tr = trees[i];
+    if (tr->device != first->device || tr->dev.vocab_size != first->dev.vocab_size ||
+        tr->dev.blank_id != first->dev.blank_id || tr->dev.eos_id >= 0)
+      return PB_EUNSUPPORTED;
+    table[static_cast<size_t>(i)] = tr->dev;
+  }
+  pb_forest* f = new (std::nothrow) pb_forest();
+  if (!f) return PB_ENOMEM;
+  int prev = 0, rc = PB_OK;
+  if (hipGetDevice(&prev) != hipSuccess || hipSetDevice(first->device) != hipSuccess) {
+    (void)hipGetLastError();
+    delete f;
+    return PB_EHIP;
+  }
+  const size_t bytes = table.size() * sizeof(pb::DeviceTree);
+  if (hipMalloc(reinterpret_cast<void**>(&f->d_table), bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    rc = PB_ENOMEM;
+  } else if (hipMemcpy(f->d_table, table.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipFree(f->d_table);
+    rc = PB_EHIP;
+  }
+  (void)hipSetDevice(prev);
+  if (rc != PB_OK) {
+    delete f;
+    return rc;
+  }
+  f->proto = first->dev;
+  f->count = n_trees;
+  f->device = first->device;
+  *out = f;
+  return PB_OK;
+}
+
+int pb_forest_free(pb_forest* forest) {
+  if (!forest) return PB_OK;
+  int rc = PB_OK, prev = 0;
+  (void)hipGetDevice(&prev);
+  (void)hipSetDevice(forest->device);
+  if (hipFree(forest->d_table) != hipSuccess) {
+    (void)hipGetLastError();
+    rc = PB_EHIP;
+  }
+  (void)hipSetDevice(prev);
+  delete forest;
+  return rc;
+}
+
+int pb_score_forest(const pb_forest* forest, const int32_t* d_tree_ids, const int32_t* d_states, int32_t B,
+                    float* d_scores, int32_t* d_next, void* hip_stream) {
+  if (!forest || B < 0) return PB_EINVAL;
+  if (B == 0) return PB_OK;
+  if (!d_tree_ids || !d_states || !d_scores) return PB_EINVAL;
+  const pb::TreePick pick{forest->d_table, d_tree_ids, forest->count};
+  return pb::launch_score(forest->proto, pick, d_states, B, d_scores, d_next, static_cast<hipStream_t>(hip_stream));
+}
+
+int pb_fuse_step_forest(const pb_forest* forest, const float* d_logp, int64_t row_stride, const int32_t* d_tree_ids,
+                        const int32_t* d_states_in, const int32_t* d_last_tokens, float alpha, int32_t B, int32_t mode,
+                        int32_t* d_tokens, int32_t* d_states_out, float* d_scores, void* hip_stream) {
+  if (!forest || B < 0) return PB_EINVAL;
+  if (mode != PB_SELECT_FUSED && mode != PB_SELECT_TWO_STAGE && mode != PB_SELECT_TWO_STAGE_CTC) return PB_EINVAL;
+  if (B == 0) return PB_OK;
+  if (!d_logp || !d_tree_ids || !d_states_in || !d_tokens || !d_states_out || !d_scores) return PB_EINVAL;
+  if (row_stride < forest->proto.vocab_size) return PB_EINVAL;
+  const pb::TreePick pick{forest->d_table, d_tree_ids, forest->count};
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (pb::wave_path_ok(forest->proto, d_logp, 0, row_stride))  // members share the vocabulary, so one answer fits all
+    return pb::launch_step_wave(forest->proto, pick, d_logp, row_stride, d_states_in, d_last_tokens, alpha, B, mode,
+                                d_tokens, d_states_out, d_scores, stream);
+  return pb::launch_fuse(forest->proto, pick, d_logp, 0, row_stride, d_states_in, d_last_tokens, alpha, 1, B, mode,
+                         d_tokens, d_states_out, d_scores, stream);
+}
+
+int pb_fuse_step_beam_forest(const pb_forest* forest, const float* d_logp, int64_t row_stride,
+                             const int32_t* d_tree_ids, const float* d_hyp_scores, const int32_t* d_states_in,
+                             float alpha, int32_t U, int32_t K, int32_t* d_tokens, int32_t* d_parents,
+                             int32_t* d_states_out, float* d_scores_out, void* hip_stream) {
+  if (!forest || U < 0 || K < 1) return PB_EINVAL;
+  if (K > 32) return PB_EUNSUPPORTED;
+  if (U == 0) return PB_OK;
+  if (!d_logp || !d_tree_ids || !d_hyp_scores || !d_states_in || !d_tokens || !d_parents || !d_states_out ||
+      !d_scores_out)
+    return PB_EINVAL;
+  if (row_stride < forest->proto.vocab_size || d_states_out == d_states_in) return PB_EINVAL;
+  if (static_cast<int64_t>(K) * forest->proto.vocab_size >= INT32_MAX) return PB_EUNSUPPORTED;
+  if (static_cast<int64_t>(U) * K > INT32_MAX) return PB_EUNSUPPORTED;
+  const pb::TreePick pick{forest->d_table, d_tree_ids, forest->count};
+  return pb::launch_beam(forest->proto, pick, d_logp, row_stride, d_hyp_scores, d_states_in, alpha, U, K, d_tokens,
+                         d_parents, d_states_out, d_scores_out, static_cast<hipStream_t>(hip_stream));
 }
 
 int pb_diag_chase(const int32_t* d_table, int64_t n, int32_t start, int32_t hops, int32_t* d_out, void* hip_stream) {

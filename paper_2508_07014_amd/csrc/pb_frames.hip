@@ -870,10 +870,10 @@ __global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, const f
   }
 }
 
-// Single step: one wave per hypothesis, no speculation.
+// Single step: one wave per hypothesis, no speculation.  With a table of trees every hypothesis names its own.
 template <int MODE, int SEL>
-__global__ void __launch_bounds__(256) step_wave_kernel(DeviceTree dt, const float* __restrict__ logp, int64_t row_stride,
-                                                        const int32_t* __restrict__ states_in,
+__global__ void __launch_bounds__(256) step_wave_kernel(DeviceTree dt, TreePick pick, const float* __restrict__ logp,
+                                                        int64_t row_stride, const int32_t* __restrict__ states_in,
                                                         const int32_t* __restrict__ last_in, float alpha, int B,
                                                         int32_t* __restrict__ tokens, int32_t* __restrict__ states_out,
                                                         float* __restrict__ scores) {
@@ -883,8 +883,10 @@ __global__ void __launch_bounds__(256) step_wave_kernel(DeviceTree dt, const flo
   if (b >= B) return;
   float* row = lds + wave * kWaveLdsFloats;
   unsigned* tags = reinterpret_cast<unsigned*>(row + kChunk);
-  const TreeView t = make_view(dt);
-  const int s = states_in[b];
+  DeviceTree mine = dt;
+  const bool tree_ok = pick_tree(pick, b, mine);
+  const TreeView t = make_view(mine);
+  const int s = tree_ok ? states_in[b] : -1;  // an unknown tree marks the hypothesis like an invalid state
   int last = -1;
   if (SEL == 2 && last_in != nullptr) last = last_in[b];
   run_frames<false, MODE, SEL>(t, logp, 0, row_stride, alpha, B, b, 0, 1, s, last, tokens, states_out, scores, row, tags,
@@ -1040,15 +1042,15 @@ bool wave_path_ok(const DeviceTree& t, const float* d_logp, int64_t frame_stride
     default: LAUNCH(2, 2); break;      \
   }
 
-int launch_step_wave(const DeviceTree& t, const float* d_logp, int64_t row_stride, const int32_t* d_states_in,
-                     const int32_t* d_last, float alpha, int32_t B, int sel, int32_t* d_tokens, int32_t* d_states_out,
+int launch_step_wave(const DeviceTree& t, const TreePick& pick, const float* d_logp, int64_t row_stride,
+                     const int32_t* d_states_in, const int32_t* d_last, float alpha, int32_t B, int sel, int32_t* d_tokens, int32_t* d_states_out,
                      float* d_scores, hipStream_t stream) {
   const int waves = B >= 1024 ? 4 : 1;  // few rows: spread them over as many CUs as possible
   const dim3 grid(static_cast<unsigned>((B + waves - 1) / waves)), block(static_cast<unsigned>(64 * waves));
   const size_t lds = static_cast<size_t>(waves) * kWaveLdsBytes;
 #define PB_LAUNCH(MODE, SEL)                                                                                      \
-  hipLaunchKernelGGL((step_wave_kernel<MODE, SEL>), grid, block, lds, stream, t, d_logp, row_stride, d_states_in, \
-                     d_last, alpha, B, d_tokens, d_states_out, d_scores)
+  hipLaunchKernelGGL((step_wave_kernel<MODE, SEL>), grid, block, lds, stream, t, pick, d_logp, row_stride,       \
+                     d_states_in, d_last, alpha, B, d_tokens, d_states_out, d_scores)
   PB_DISPATCH(mode_of(t.vocab_size), sel, PB_LAUNCH)
 #undef PB_LAUNCH
   return hipGetLastError() == hipSuccess ? PB_OK : PB_EHIP;

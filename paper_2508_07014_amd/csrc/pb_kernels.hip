@@ -142,14 +142,23 @@ __global__ void __launch_bounds__(256) score_eos_kernel(DeviceTree t, const int3
 // thread).  A hypothesis in the root state has no chain: its row is
 // the root row itself and skips LDS and barriers.
 template <int VEC>
-__global__ void __launch_bounds__(256) score_kernel(DeviceTree t, const int32_t* __restrict__ states, int B,
-                                                    float* __restrict__ scores, int32_t* __restrict__ next,
+__global__ void __launch_bounds__(256) score_kernel(DeviceTree t0, TreePick pick, const int32_t* __restrict__ states,
+                                                    int B, float* __restrict__ scores, int32_t* __restrict__ next,
                                                     int tile, int tiles, int per) {
   extern __shared__ u64 row[];
   const int grp = blockIdx.x / tiles;
   const int v0 = (blockIdx.x - grp * tiles) * tile;
-  const int V = t.vocab_size;
+  const int V = t0.vocab_size;
   const int n = min(tile, V - v0);
+  DeviceTree t = t0;
+  if (!pick_tree(pick, grp, t)) {  // with a table of trees every workgroup has one hypothesis (per == 1)
+    const size_t base = static_cast<size_t>(grp) * V + v0;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+      scores[base + i] = NAN;
+      if (next) next[base + i] = -1;
+    }
+    return;
+  }
   constexpr int kMaxSlots = kScoreTile / (256 * 4);  // float4 groups per thread
   float4 rs[kMaxSlots];
   int4 rn[kMaxSlots];
@@ -299,8 +308,9 @@ __device__ __forceinline__ void fused_row(const DeviceTree& t, const float* __re
 // sequence with the state (and, under the CTC rule, the previous label) carried in registers.
 // sel: 0 single-stage, 1 two-stage, 2 two-stage with the CTC repeat rule (Sec. II-C).
 template <int VEC>
-__global__ void __launch_bounds__(1024) fuse_kernel(DeviceTree t, const float* __restrict__ logp, int64_t frame_stride,
-                                                    int64_t row_stride, const int32_t* __restrict__ states0,
+__global__ void __launch_bounds__(1024) fuse_kernel(DeviceTree t0, TreePick pick, const float* __restrict__ logp,
+                                                    int64_t frame_stride, int64_t row_stride,
+                                                    const int32_t* __restrict__ states0,
                                                     const int32_t* __restrict__ last0, float alpha, int T, int B, int sel,
                                                     int32_t* __restrict__ tokens, int32_t* __restrict__ states,
                                                     float* __restrict__ scores, int chunk) {
@@ -309,8 +319,10 @@ __global__ void __launch_bounds__(1024) fuse_kernel(DeviceTree t, const float* _
   __shared__ int si[16];
   __shared__ int s_next;
   const int b = blockIdx.x;
+  DeviceTree t = t0;
+  const bool tree_ok = pick_tree(pick, b, t);
   const int V = t.vocab_size;
-  int s = states0[b];
+  int s = tree_ok ? states0[b] : -1;  // an unknown tree marks the hypothesis like an invalid state
   int last = (sel == 2 && last0 != nullptr) ? last0[b] : -1;
   for (int f = 0; f < T; ++f) {
     const size_t o = static_cast<size_t>(f) * B + b;
@@ -424,8 +436,9 @@ struct TopList {
 };
 
 template <int KC, int VEC>
-__global__ void __launch_bounds__(1024) beam_kernel(DeviceTree t, const float* __restrict__ logp, int64_t row_stride,
-                                                    const float* __restrict__ hyp, const int32_t* __restrict__ states_in,
+__global__ void __launch_bounds__(1024) beam_kernel(DeviceTree t0, TreePick pick, const float* __restrict__ logp,
+                                                    int64_t row_stride, const float* __restrict__ hyp,
+                                                    const int32_t* __restrict__ states_in,
                                                     float alpha, int K, int32_t* __restrict__ tokens,
                                                     int32_t* __restrict__ parents, int32_t* __restrict__ states_out,
                                                     float* __restrict__ scores_out, int chunk) {
@@ -433,8 +446,9 @@ __global__ void __launch_bounds__(1024) beam_kernel(DeviceTree t, const float* _
   __shared__ float sv[16];
   __shared__ int si[16];
   const int u = blockIdx.x;
+  DeviceTree t = t0;
+  bool valid = pick_tree(pick, u, t);  // one tree per utterance
   const int V = t.vocab_size;
-  bool valid = true;
   for (int k = 0; k < K; ++k)
     valid = valid && static_cast<unsigned>(states_in[u * K + k]) < static_cast<unsigned>(t.num_states);
   if (!valid) {
@@ -536,32 +550,32 @@ inline int check_launch() { return hipGetLastError() == hipSuccess ? PB_OK : PB_
 
 }  // namespace
 
-int launch_score(const DeviceTree& t, const int32_t* d_states, int32_t B, float* d_scores, int32_t* d_next,
-                 hipStream_t stream) {
+int launch_score(const DeviceTree& t, const TreePick& pick, const int32_t* d_states, int32_t B, float* d_scores,
+                 int32_t* d_next, hipStream_t stream) {
   const int V = t.vocab_size;
   const int tile = V < kScoreTile ? ((V + 3) & ~3) : kScoreTile;
   const int tiles = (V + tile - 1) / tile;
   // hypotheses per workgroup: one while the launch is small, up to four once 4096 workgroups remain
   const int64_t wgs = static_cast<int64_t>(B) * tiles;
-  const int per = wgs >= 4 * 4096 ? 4 : (wgs >= 2 * 4096 ? 2 : 1);
+  const int per = pick.table ? 1 : (wgs >= 4 * 4096 ? 4 : (wgs >= 2 * 4096 ? 2 : 1));
   const int64_t groups = (static_cast<int64_t>(B) + per - 1) / per;
   if (groups * tiles > INT32_MAX) return PB_EUNSUPPORTED;
   const dim3 grid(static_cast<unsigned>(groups * tiles));
   const size_t lds = static_cast<size_t>(tile) * sizeof(u64);
   const bool vec = (V % 4 == 0) && aligned16(d_scores) && (d_next == nullptr || aligned16(d_next));
   if (vec)
-    hipLaunchKernelGGL(score_kernel<4>, grid, dim3(256), lds, stream, t, d_states, B, d_scores, d_next, tile, tiles,
-                       per);
+    hipLaunchKernelGGL(score_kernel<4>, grid, dim3(256), lds, stream, t, pick, d_states, B, d_scores, d_next, tile,
+                       tiles, per);
   else
-    hipLaunchKernelGGL(score_kernel<1>, grid, dim3(256), lds, stream, t, d_states, B, d_scores, d_next, tile, tiles,
-                       per);
+    hipLaunchKernelGGL(score_kernel<1>, grid, dim3(256), lds, stream, t, pick, d_states, B, d_scores, d_next, tile,
+                       tiles, per);
   if (t.eos_id >= 0)
     hipLaunchKernelGGL(score_eos_kernel, dim3(static_cast<unsigned>(B)), dim3(256), 0, stream, t, d_states, d_scores,
                        d_next);
   return check_launch();
 }
 
-int launch_fuse(const DeviceTree& t, const float* d_logp, int64_t frame_stride, int64_t row_stride,
+int launch_fuse(const DeviceTree& t, const TreePick& pick, const float* d_logp, int64_t frame_stride, int64_t row_stride,
                 const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B, int sel,
                 int32_t* d_tokens, int32_t* d_states, float* d_scores, hipStream_t stream) {
   const int V = t.vocab_size;
@@ -570,10 +584,10 @@ int launch_fuse(const DeviceTree& t, const float* d_logp, int64_t frame_stride, 
   const bool vec = (V % 4 == 0) && (row_stride % 4 == 0) && (frame_stride % 4 == 0) && aligned16(d_logp);
   const dim3 grid(static_cast<unsigned>(B)), block(static_cast<unsigned>(pick_threads(V)));
   if (vec)
-    hipLaunchKernelGGL(fuse_kernel<4>, grid, block, lds, stream, t, d_logp, frame_stride, row_stride, d_states0, d_last0,
+    hipLaunchKernelGGL(fuse_kernel<4>, grid, block, lds, stream, t, pick, d_logp, frame_stride, row_stride, d_states0, d_last0,
                        alpha, T, B, sel, d_tokens, d_states, d_scores, chunk);
   else
-    hipLaunchKernelGGL(fuse_kernel<1>, grid, block, lds, stream, t, d_logp, frame_stride, row_stride, d_states0, d_last0,
+    hipLaunchKernelGGL(fuse_kernel<1>, grid, block, lds, stream, t, pick, d_logp, frame_stride, row_stride, d_states0, d_last0,
                        alpha, T, B, sel, d_tokens, d_states, d_scores, chunk);
   return check_launch();
 }
@@ -584,7 +598,7 @@ int launch_chase(const int32_t* d_table, int32_t start, int32_t hops, int32_t* d
 }
 
 template <int KC>
-static int launch_beam_kc(const DeviceTree& t, const float* d_logp, int64_t row_stride, const float* d_hyp,
+static int launch_beam_kc(const DeviceTree& t, const TreePick& pick, const float* d_logp, int64_t row_stride, const float* d_hyp,
                           const int32_t* d_states_in, float alpha, int32_t U, int32_t K, int32_t* d_tokens,
                           int32_t* d_parents, int32_t* d_states_out, float* d_scores_out, hipStream_t stream) {
   const int V = t.vocab_size;
@@ -593,19 +607,19 @@ static int launch_beam_kc(const DeviceTree& t, const float* d_logp, int64_t row_
   const bool vec = (V % 4 == 0) && (row_stride % 4 == 0) && aligned16(d_logp);
   const dim3 grid(static_cast<unsigned>(U)), block(static_cast<unsigned>(pick_threads(V)));
   if (vec)
-    hipLaunchKernelGGL((beam_kernel<KC, 4>), grid, block, lds, stream, t, d_logp, row_stride, d_hyp, d_states_in, alpha,
+    hipLaunchKernelGGL((beam_kernel<KC, 4>), grid, block, lds, stream, t, pick, d_logp, row_stride, d_hyp, d_states_in, alpha,
                        K, d_tokens, d_parents, d_states_out, d_scores_out, chunk);
   else
-    hipLaunchKernelGGL((beam_kernel<KC, 1>), grid, block, lds, stream, t, d_logp, row_stride, d_hyp, d_states_in, alpha,
+    hipLaunchKernelGGL((beam_kernel<KC, 1>), grid, block, lds, stream, t, pick, d_logp, row_stride, d_hyp, d_states_in, alpha,
                        K, d_tokens, d_parents, d_states_out, d_scores_out, chunk);
   return check_launch();
 }
 
-int launch_beam(const DeviceTree& t, const float* d_logp, int64_t row_stride, const float* d_hyp,
+int launch_beam(const DeviceTree& t, const TreePick& pick, const float* d_logp, int64_t row_stride, const float* d_hyp,
                 const int32_t* d_states_in, float alpha, int32_t U, int32_t K, int32_t* d_tokens, int32_t* d_parents,
                 int32_t* d_states_out, float* d_scores_out, hipStream_t stream) {
 #define PB_BEAM(KC)                                                                                            \
-  return launch_beam_kc<KC>(t, d_logp, row_stride, d_hyp, d_states_in, alpha, U, K, d_tokens, d_parents, \
+  return launch_beam_kc<KC>(t, pick, d_logp, row_stride, d_hyp, d_states_in, alpha, U, K, d_tokens, d_parents, \
                             d_states_out, d_scores_out, stream)
   if (K <= 1) PB_BEAM(1);
   if (K <= 2) PB_BEAM(2);

@@ -6,15 +6,24 @@
 
 namespace pb {
 
+// The tree of row i: `t` as passed, or table[ids[i]] when a table is given.  False for an id outside the table.
+__device__ __forceinline__ bool pick_tree(const TreePick& p, int i, DeviceTree& t) {
+  if (p.table == nullptr) return true;
+  const int32_t id = p.ids[i];
+  if (static_cast<uint32_t>(id) >= static_cast<uint32_t>(p.count)) return false;
+  t = p.table[id];
+  return true;
+}
+
 constexpr int kMaxChunk = 8192;   // tokens per LDS pass of the fused kernels (64 KiB of 8-byte entries)
 constexpr int kScoreTile = 2048;  // tokens per workgroup of the score kernel (16 KiB of LDS)
 
-int launch_score(const DeviceTree& t, const int32_t* d_states, int32_t B, float* d_scores, int32_t* d_next,
-                 hipStream_t stream);
+int launch_score(const DeviceTree& t, const TreePick& pick, const int32_t* d_states, int32_t B, float* d_scores,
+                 int32_t* d_next, hipStream_t stream);
 
 // T == 1 with frame_stride == 0 is the single step.  sel is an enum pb_select_mode value; d_last0 (previous
 // labels, CTC rule only) may be null.
-int launch_fuse(const DeviceTree& t, const float* d_logp, int64_t frame_stride, int64_t row_stride,
+int launch_fuse(const DeviceTree& t, const TreePick& pick, const float* d_logp, int64_t frame_stride, int64_t row_stride,
                 const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B, int sel,
                 int32_t* d_tokens, int32_t* d_states, float* d_scores, hipStream_t stream);
 
@@ -28,7 +37,8 @@ constexpr int kMaxSegments = 64;     // segments per hypothesis (one lane each i
 
 bool wave_path_ok(const DeviceTree& t, const float* d_logp, int64_t frame_stride, int64_t row_stride);
 int prepare_wave_kernels();  // once per device, after the device has been made current
-int launch_step_wave(const DeviceTree& t, const float* d_logp, int64_t row_stride, const int32_t* d_states_in,
+int launch_step_wave(const DeviceTree& t, const TreePick& pick, const float* d_logp, int64_t row_stride,
+                     const int32_t* d_states_in,
                      const int32_t* d_last, float alpha, int32_t B, int sel, int32_t* d_tokens, int32_t* d_states_out,
                      float* d_scores, hipStream_t stream);
 int launch_frames_wave(const DeviceTree& t, const float* d_logp, int64_t frame_stride, int64_t row_stride,
@@ -44,7 +54,7 @@ int launch_beam_wave(const DeviceTree& t, const float* d_logp, int64_t row_strid
                      const int32_t* d_states_in, float alpha, int32_t U, int32_t K, int32_t* d_tokens,
                      int32_t* d_parents, int32_t* d_states_out, float* d_scores_out, hipStream_t stream);
 
-int launch_beam(const DeviceTree& t, const float* d_logp, int64_t row_stride, const float* d_hyp,
+int launch_beam(const DeviceTree& t, const TreePick& pick, const float* d_logp, int64_t row_stride, const float* d_hyp,
                 const int32_t* d_states_in, float alpha, int32_t U, int32_t K, int32_t* d_tokens, int32_t* d_parents,
                 int32_t* d_states_out, float* d_scores_out, hipStream_t stream);
 

@@ -49,6 +49,14 @@ struct DeviceTree {
   int32_t eos_id = -1;
 };
 
+// Per-row choice among several trees (a different context list per hypothesis or utterance): row i uses
+// table[ids[i]].  A null table means "the one tree passed beside it".
+struct TreePick {
+  const DeviceTree* table = nullptr;  // device array of `count` trees
+  const int32_t* ids = nullptr;       // device array, one id per hypothesis (beam step: per utterance)
+  int32_t count = 0;
+};
+
 struct HostTree {
   int32_t vocab_size = 0, blank_id = -1, eos_id = -1;
   int32_t max_depth = 0, max_fail_chain = 0, root_degree = 0;
@@ -66,6 +74,13 @@ int compile_tree(const int32_t* tokens, const int64_t* offsets, int64_t n_phrase
                  const pb_build_opts& opts, HostTree& out);
 
 }  // namespace pb
+
+struct pb_forest {
+  pb::DeviceTree* d_table = nullptr;  // device copy of the members' DeviceTree records
+  pb::DeviceTree proto;               // vocabulary size and blank id common to all members
+  int32_t count = 0;
+  int device = -1;
+};
 
 struct pb_tree {
   pb::HostTree host;
