@@ -218,7 +218,7 @@ int pb_fuse_step_beam(const pb_tree* tree, const float* d_logp, int64_t row_stri
  *   pb_forest_build groups n_trees trees built for the same device with the same vocab_size and blank_id
  *   and without an EOS rule (PB_EUNSUPPORTED otherwise; PB_EINVAL for null arguments, n_trees < 1 or a
  *   host-only tree).  The forest refers to the trees' device arrays: free it before them.
- *   The *_forest calls are pb_score, pb_fuse_step_select and pb_fuse_step_beam with one more device
+ *   The *_forest calls are pb_score, pb_fuse_step_select, pb_fuse_frames_select and pb_fuse_step_beam with one more device
  *   array: d_tree_ids int32[B] (beam: int32[U]) names the member tree of every row; states are states
  *   of that tree.  An id outside [0, n_trees) marks the row's outputs like an invalid state (-1 / NaN).
  */
@@ -230,6 +230,10 @@ int pb_score_forest(const pb_forest* forest, const int32_t* d_tree_ids, const in
 int pb_fuse_step_forest(const pb_forest* forest, const float* d_logp, int64_t row_stride, const int32_t* d_tree_ids,
                         const int32_t* d_states_in, const int32_t* d_last_tokens, float alpha, int32_t B, int32_t mode,
                         int32_t* d_tokens, int32_t* d_states_out, float* d_scores, void* hip_stream);
+int pb_fuse_frames_forest(const pb_forest* forest, const float* d_logp, int64_t frame_stride, int64_t row_stride,
+                          const int32_t* d_tree_ids, const int32_t* d_states0, const int32_t* d_last0, float alpha,
+                          int32_t T, int32_t B, int32_t mode, int32_t* d_tokens, int32_t* d_states, float* d_scores,
+                          void* hip_stream);
 int pb_fuse_step_beam_forest(const pb_forest* forest, const float* d_logp, int64_t row_stride,
                              const int32_t* d_tree_ids, const float* d_hyp_scores, const int32_t* d_states_in,
                              float alpha, int32_t U, int32_t K, int32_t* d_tokens, int32_t* d_parents,

@@ -19,7 +19,7 @@ PB_SELECT_FUSED, PB_SELECT_TWO_STAGE, PB_SELECT_TWO_STAGE_CTC = 0, 1, 2
 
 EXPORTS = ["pb_build", "pb_free", "pb_info", "pb_host_arrays", "pb_state_prefix", "pb_score", "pb_fuse_step",
            "pb_fuse_frames", "pb_fuse_step_select", "pb_fuse_frames_select", "pb_fuse_step_beam", "pb_diag_chase", "pb_forest_build", "pb_forest_free", "pb_score_forest",
-           "pb_fuse_step_forest", "pb_fuse_step_beam_forest", "pb_strerror"]
+           "pb_fuse_step_forest", "pb_fuse_frames_forest", "pb_fuse_step_beam_forest", "pb_strerror"]
 
 
 class PbError(RuntimeError):
@@ -102,6 +102,9 @@ def load():
     lib.pb_score_forest.argtypes = [vp, vp, vp, C.c_int32, vp, vp, vp]
     lib.pb_fuse_step_forest.restype = C.c_int
     lib.pb_fuse_step_forest.argtypes = [vp, vp, C.c_int64, vp, vp, vp, C.c_float, C.c_int32, C.c_int32, vp, vp, vp, vp]
+    lib.pb_fuse_frames_forest.restype = C.c_int
+    lib.pb_fuse_frames_forest.argtypes = [vp, vp, C.c_int64, C.c_int64, vp, vp, vp, C.c_float, C.c_int32, C.c_int32,
+                                          C.c_int32, vp, vp, vp, vp]
     lib.pb_fuse_step_beam_forest.restype = C.c_int
     lib.pb_fuse_step_beam_forest.argtypes = [vp, vp, C.c_int64, vp, vp, vp, C.c_float, C.c_int32, C.c_int32, vp, vp, vp,
                                              vp, vp]
@@ -281,6 +284,13 @@ def pb_fuse_step_forest(forest: Forest, d_logp, row_stride: int, d_tree_ids, d_s
     _check(load().pb_fuse_step_forest(forest.handle, _dptr(d_logp), row_stride, _dptr(d_tree_ids), _dptr(d_states_in),
                                       _dptr(d_last_tokens), alpha, B, mode, _dptr(d_tokens), _dptr(d_states_out),
                                       _dptr(d_scores), stream or None), "pb_fuse_step_forest")
+
+
+def pb_fuse_frames_forest(forest: Forest, d_logp, frame_stride: int, row_stride: int, d_tree_ids, d_states0, d_last0,
+                          alpha: float, T: int, B: int, mode: int, d_tokens, d_states, d_scores, stream: int = 0):
+    _check(load().pb_fuse_frames_forest(forest.handle, _dptr(d_logp), frame_stride, row_stride, _dptr(d_tree_ids),
+                                        _dptr(d_states0), _dptr(d_last0), alpha, T, B, mode, _dptr(d_tokens),
+                                        _dptr(d_states), _dptr(d_scores), stream or None), "pb_fuse_frames_forest")
 
 
 def pb_fuse_step_beam_forest(forest: Forest, d_logp, row_stride: int, d_tree_ids, d_hyp_scores, d_states_in,

@@ -197,7 +197,7 @@ int pb_fuse_frames_select(const pb_tree* tree, const float* d_logp, int64_t fram
   if (row_stride < tree->dev.vocab_size || frame_stride < 0) return PB_EINVAL;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (pb::wave_path_ok(tree->dev, d_logp, frame_stride, row_stride))
-    return pb::launch_frames_wave(tree->dev, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, mode,
+    return pb::launch_frames_wave(tree->dev, pb::TreePick{}, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, mode,
                                   d_tokens, d_states, d_scores, stream);
   return pb::launch_fuse(tree->dev, pb::TreePick{}, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, mode, d_tokens,
                          d_states, d_scores, stream);
@@ -310,6 +310,24 @@ int pb_fuse_step_forest(const pb_forest* forest, const float* d_logp, int64_t ro
                                 d_tokens, d_states_out, d_scores, stream);
   return pb::launch_fuse(forest->proto, pick, d_logp, 0, row_stride, d_states_in, d_last_tokens, alpha, 1, B, mode,
                          d_tokens, d_states_out, d_scores, stream);
+}
+
+int pb_fuse_frames_forest(const pb_forest* forest, const float* d_logp, int64_t frame_stride, int64_t row_stride,
+                          const int32_t* d_tree_ids, const int32_t* d_states0, const int32_t* d_last0, float alpha,
+                          int32_t T, int32_t B, int32_t mode, int32_t* d_tokens, int32_t* d_states, float* d_scores,
+                          void* hip_stream) {
+  if (!forest || B < 0 || T < 0) return PB_EINVAL;
+  if (mode != PB_SELECT_FUSED && mode != PB_SELECT_TWO_STAGE && mode != PB_SELECT_TWO_STAGE_CTC) return PB_EINVAL;
+  if (B == 0 || T == 0) return PB_OK;
+  if (!d_logp || !d_tree_ids || !d_states0 || !d_tokens || !d_states || !d_scores) return PB_EINVAL;
+  if (row_stride < forest->proto.vocab_size || frame_stride < 0) return PB_EINVAL;
+  const pb::TreePick pick{forest->d_table, d_tree_ids, forest->count};
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (pb::wave_path_ok(forest->proto, d_logp, frame_stride, row_stride))
+    return pb::launch_frames_wave(forest->proto, pick, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B,
+                                  mode, d_tokens, d_states, d_scores, stream);
+  return pb::launch_fuse(forest->proto, pick, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, mode,
+                         d_tokens, d_states, d_scores, stream);
 }
 
 int pb_fuse_step_beam_forest(const pb_forest* forest, const float* d_logp, int64_t row_stride,

@@ -771,8 +771,8 @@ constexpr size_t kWaveLdsBytes = kWaveLdsFloats * sizeof(float);
 // Pass 1: chain (b, j) decodes segment j of hypothesis b; j = 0 starts from states0[b] and the
 // caller's previous label (exact), j > 0 from the root with no previous label (speculative).
 // One wave per chain.
-template <int MODE, int SEL>
-__global__ void __launch_bounds__(256, 4) frames_spec_kernel(DeviceTree dt, const float* __restrict__ logp,
+template <int MODE, int SEL, bool FOREST>
+__global__ void __launch_bounds__(256, 4) frames_spec_kernel(DeviceTree dt, TreePick pick, const float* __restrict__ logp,
                                                           int64_t frame_stride, int64_t row_stride,
                                                           const int32_t* __restrict__ states0,
                                                           const int32_t* __restrict__ last0, float alpha, int T, int B,
@@ -785,13 +785,17 @@ __global__ void __launch_bounds__(256, 4) frames_spec_kernel(DeviceTree dt, cons
   const int j = chain / B, b = chain - j * B;
   float* row = lds + wave * kWaveLdsFloats;
   unsigned* tags = reinterpret_cast<unsigned*>(row + kChunk);
-  const TreeView t = make_view(dt);
+  DeviceTree mine = dt;
+  bool tree_ok = true;
+  if constexpr (FOREST) tree_ok = pick_tree(pick, b, mine);  // a table of trees: hypothesis b names its own
+  const TreeView t = make_view(mine);
   const int f0 = j * seg_len, f1 = min(T, f0 + seg_len);
   int s = 0, last = -1;
   if (j == 0) {
     s = states0[b];
     if (SEL == 2 && last0 != nullptr) last = last0[b];
   }
+  if (!tree_ok) s = -1;  // an unknown tree marks every frame of the hypothesis like an invalid state
   run_frames<false, MODE, SEL>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, tokens, states, scores,
                                row, tags, lane);
 }
@@ -801,8 +805,8 @@ __global__ void __launch_bounds__(256, 4) frames_spec_kernel(DeviceTree dt, cons
 //       under the CTC rule, last label) until the stored trajectory is met;
 //   (b) the outcome at the end of segment j-1 is then compared, for all segments at once, with the
 //       one segment j was re-run from, and the stale segments are re-run, in parallel rounds.
-template <int MODE, int SEL>
-__global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, const float* __restrict__ logp,
+template <int MODE, int SEL, bool FOREST>
+__global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, TreePick pick, const float* __restrict__ logp,
                                                           int64_t frame_stride, int64_t row_stride, float alpha, int T,
                                                           int B, int seg_len, int nseg, int32_t* __restrict__ tokens,
                                                           int32_t* __restrict__ states, float* __restrict__ scores) {
@@ -813,7 +817,11 @@ __global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, const f
   const int b = blockIdx.x;
   float* row = lds + wave * kWaveLdsFloats;
   unsigned* tags = reinterpret_cast<unsigned*>(row + kChunk);
-  const TreeView t = make_view(dt);
+  DeviceTree mine = dt;
+  if constexpr (FOREST) {
+    if (!pick_tree(pick, b, mine)) return;  // pass 1 has marked every frame of this hypothesis (the whole workgroup leaves)
+  }
+  const TreeView t = make_view(mine);
   auto rerun = [&](int seg, int s, int last) {
     const int f0 = seg * seg_len, f1 = min(T, f0 + seg_len);
     run_frames<true, MODE, SEL>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, tokens, states, scores,
@@ -1056,7 +1064,8 @@ int launch_step_wave(const DeviceTree& t, const TreePick& pick, const float* d_l
   return hipGetLastError() == hipSuccess ? PB_OK : PB_EHIP;
 }
 
-int launch_frames_wave(const DeviceTree& t, const float* d_logp, int64_t frame_stride, int64_t row_stride,
+int launch_frames_wave(const DeviceTree& t, const TreePick& pick, const float* d_logp, int64_t frame_stride,
+                       int64_t row_stride,
                        const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B, int sel,
                        int32_t* d_tokens, int32_t* d_states, float* d_scores, hipStream_t stream) {
   // Segments: enough concurrent chains to cover the memory latency, at most kMaxSegments per
@@ -1072,21 +1081,39 @@ int launch_frames_wave(const DeviceTree& t, const float* d_logp, int64_t frame_s
   if (blocks > INT32_MAX) return PB_EUNSUPPORTED;
   const size_t lds = static_cast<size_t>(waves) * kWaveLdsBytes;
   const int mode = mode_of(t.vocab_size);
-#define PB_LAUNCH(MODE, SEL)                                                                                        \
-  hipLaunchKernelGGL((frames_spec_kernel<MODE, SEL>), dim3(static_cast<unsigned>(blocks)), dim3(64 * waves), lds,   \
-                     stream, t, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, seg_len, nseg,   \
-                     d_tokens, d_states, d_scores)
-  PB_DISPATCH(mode, sel, PB_LAUNCH)
+  const bool forest = pick.table != nullptr;
+#define PB_SPEC(MODE, SEL, FOREST)                                                                                   \
+  hipLaunchKernelGGL((frames_spec_kernel<MODE, SEL, FOREST>), dim3(static_cast<unsigned>(blocks)), dim3(64 * waves), \
+                     lds, stream, t, pick, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B,        \
+                     seg_len, nseg, d_tokens, d_states, d_scores)
+#define PB_LAUNCH(MODE, SEL) PB_SPEC(MODE, SEL, false)
+#define PB_LAUNCH_F(MODE, SEL) PB_SPEC(MODE, SEL, true)
+  if (forest) {
+    PB_DISPATCH(mode, sel, PB_LAUNCH_F)
+  } else {
+    PB_DISPATCH(mode, sel, PB_LAUNCH)
+  }
 #undef PB_LAUNCH
+#undef PB_LAUNCH_F
+#undef PB_SPEC
   if (hipGetLastError() != hipSuccess) return PB_EHIP;
   if (nseg > 1) {
     int fw = nseg - 1 < g_fix_waves ? nseg - 1 : g_fix_waves;
     const size_t lds2 = static_cast<size_t>(fw) * kWaveLdsBytes;
-#define PB_LAUNCH(MODE, SEL)                                                                                      \
-  hipLaunchKernelGGL((frames_fix_kernel<MODE, SEL>), dim3(static_cast<unsigned>(B)), dim3(64 * fw), lds2, stream, \
-                     t, d_logp, frame_stride, row_stride, alpha, T, B, seg_len, nseg, d_tokens, d_states, d_scores)
-    PB_DISPATCH(mode, sel, PB_LAUNCH)
+#define PB_FIX(MODE, SEL, FOREST)                                                                                     \
+  hipLaunchKernelGGL((frames_fix_kernel<MODE, SEL, FOREST>), dim3(static_cast<unsigned>(B)), dim3(64 * fw), lds2,     \
+                     stream, t, pick, d_logp, frame_stride, row_stride, alpha, T, B, seg_len, nseg, d_tokens,         \
+                     d_states, d_scores)
+#define PB_LAUNCH(MODE, SEL) PB_FIX(MODE, SEL, false)
+#define PB_LAUNCH_F(MODE, SEL) PB_FIX(MODE, SEL, true)
+    if (forest) {
+      PB_DISPATCH(mode, sel, PB_LAUNCH_F)
+    } else {
+      PB_DISPATCH(mode, sel, PB_LAUNCH)
+    }
 #undef PB_LAUNCH
+#undef PB_LAUNCH_F
+#undef PB_FIX
     if (hipGetLastError() != hipSuccess) return PB_EHIP;
   }
   return PB_OK;
@@ -1124,7 +1151,9 @@ int prepare_wave_kernels() {
     const int bytes = waves * static_cast<int>(kWaveLdsBytes);
     const hipFuncAttribute attr = hipFuncAttributeMaxDynamicSharedMemorySize;
     bool ok = true;
-#define PB_SET(MODE, SEL)   ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(frames_fix_kernel<MODE, SEL>), attr, bytes) == hipSuccess
+#define PB_SET(MODE, SEL)                                                                                              \
+  ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(frames_fix_kernel<MODE, SEL, false>), attr, bytes) == hipSuccess && \
+       hipFuncSetAttribute(reinterpret_cast<const void*>(frames_fix_kernel<MODE, SEL, true>), attr, bytes) == hipSuccess
     for (int ms = 0; ms < 9; ++ms) PB_DISPATCH(ms / 3, ms % 3, PB_SET)
 #undef PB_SET
     if (!ok) {

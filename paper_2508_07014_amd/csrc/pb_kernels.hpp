@@ -41,7 +41,8 @@ int launch_step_wave(const DeviceTree& t, const TreePick& pick, const float* d_l
                      const int32_t* d_states_in,
                      const int32_t* d_last, float alpha, int32_t B, int sel, int32_t* d_tokens, int32_t* d_states_out,
                      float* d_scores, hipStream_t stream);
-int launch_frames_wave(const DeviceTree& t, const float* d_logp, int64_t frame_stride, int64_t row_stride,
+int launch_frames_wave(const DeviceTree& t, const TreePick& pick, const float* d_logp, int64_t frame_stride,
+                       int64_t row_stride,
                        const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B, int sel,
                        int32_t* d_tokens, int32_t* d_states, float* d_scores, hipStream_t stream);
 

@@ -104,3 +104,30 @@ def test_forest_build_rejects_mismatched_trees():
             pb.pb_forest_build(bad)
         assert e.value.code == code
     pb.pb_forest_free(pb.pb_forest_build([a, a]))
+
+
+@pytest.mark.parametrize("V,T,B", [(128, 50, 9), (1024, 150, 12), (2048, 20, 5), (130, 30, 7)])
+def test_forest_frames(V, T, B):
+    """All frames in one call, a tree per hypothesis: wave kernels (V % 4 == 0) and the workgroup kernel."""
+    ots, forest = make_forest(V)
+    rng = np.random.default_rng(T)
+    ids = rng.integers(0, len(ots), B).astype(np.int32)
+    ids[3] = 5                                # unknown tree: every frame of the hypothesis is marked
+    s0 = np.array([rng.integers(0, ots[i].num_states) if i < len(ots) else 0 for i in ids], np.int32)
+    logp = W.sticky_logp(V + T, T, B, V, 0, grid=None, bump=6.0)
+    for mode in (SELECT_FUSED, SELECT_TWO_STAGE_CTC):
+        d_tok = torch.full((T, B), -5, dtype=torch.int32, device=DEV)
+        d_st = torch.full((T, B), -5, dtype=torch.int32, device=DEV)
+        d_sc = torch.zeros((T, B), dtype=torch.float32, device=DEV)
+        pb.pb_fuse_frames_forest(forest, dev(logp), B * V, V, dev(ids), dev(s0), None, 0.6, T, B, mode, d_tok, d_st, d_sc,
+                                 stream_ptr())
+        torch.cuda.synchronize()
+        tok, st, sc = d_tok.cpu().numpy(), d_st.cpu().numpy(), d_sc.cpu().numpy()
+        for i, ot in enumerate(ots):
+            cols = np.flatnonzero(ids == i)
+            if len(cols) == 0:
+                continue
+            want = ot.fuse_frames_select(np.ascontiguousarray(logp[:, cols]), s0[cols], None, 0.6, mode)
+            assert np.array_equal(tok[:, cols], want[0]) and np.array_equal(st[:, cols], want[1])
+            assert_scores(sc[:, cols], want[2])
+        assert np.all(tok[:, 3] == -1) and np.all(st[:, 3] == -1) and np.all(np.isnan(sc[:, 3]))
