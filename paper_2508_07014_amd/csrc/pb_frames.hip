@@ -39,6 +39,7 @@
 #include <climits>
 #include <cmath>
 #include <cstdint>
+#include <type_traits>
 
 #include "pb_kernels.hpp"
 
@@ -277,7 +278,7 @@ __device__ __forceinline__ void rebuild_base_boost(const TreeView& t, int lane, 
 //   row / tags  this wave's LDS copy of the row and its token marks
 //   last  label of the previous frame (SEL == 2 only; any value outside [0, V) = none)
 //   need_record  false when no frame follows: the record of the next state is then not fetched
-template <bool FULL, int SEL, typename NextRow>
+template <bool FULL, int SEL, int EARLY, typename NextRow>
 __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const float (&x)[16], float (&c)[16],
                                          float& c_p, float alpha, float* row, unsigned* tags, int lane, int last,
                                          bool need_record, NextRow&& next_row, float& out_val, int& out_tok) {
@@ -286,10 +287,16 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
   const bool chain = (s != 0);
   const bool multi = chain && rec0.fail != 0;
   // Vector loads retire in order, so a wait for arcs also waits for every row requested before them.
-  // The first 64 arcs of the state are therefore requested first and the row prefetch right after:
+  // The first arcs of the state are therefore requested first and the row prefetch right after:
   // the wait for these arcs leaves the prefetch in flight.
-  ArcRec a0{0, 0.0f};
-  if (chain && rec0.count > 0) a0 = t.arc[rec0.begin + min(lane, rec0.count - 1)];
+  // (Requested without a condition, so that no merge of control flow forces an early wait: for a state
+  // without arcs, or the last state of the table, the clamped index reads the entry at arc_begin, which
+  // lies inside the tree's allocation -- the arc table is followed by the dense root row -- and is
+  // never used.)
+  constexpr int kEarly = EARLY;  // batches of 64 arcs requested up front
+  ArcRec early[kEarly];
+#pragma unroll
+  for (int q = 0; q < kEarly; ++q) early[q] = t.arc[rec0.begin + max(0, min(64 * q + lane, rec0.count - 1))];
   next_row();
   if constexpr (SEL != 0) {
     // stage 1: selection without boosting; a blank (or a CTC repeat) is emitted as it is
@@ -336,37 +343,52 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
     bool hit_vb = false;
     if (chain) {
       if (multi) tags_clear(tags, lane);
+      // one arc per lane: `a` with its child state, on chain level `level` with accumulated backoff p
+      auto eval = [&](const ArcRec& a, bool valid, int child, float p, int level) {
+        const int tk = valid ? a.token : 0;  // an unused entry may hold anything: keep the LDS index in range
+        bool shadowed = !valid;
+        if (SEL == 2) shadowed = shadowed || tk == excl;
+        if (multi) {
+          if (level > 0) shadowed = shadowed || tag_test(tags, tk);  // a deeper chain state owns this token
+          if (valid) tag_set(tags, tk);
+        }
+        hit_vb = hit_vb || (valid && tk == vb);
+        const float fa = __fadd_rn(row[tk], __fmul_rn(alpha, __fadd_rn(p, a.score)));
+        const bool take = !shadowed && (fa > bf || (fa == bf && tk < btok));
+        bf = take ? fa : bf;
+        btok = take ? tk : btok;
+        bchild = take ? child : bchild;
+      };
       Rec r = rec0;
       float p = 0.0f;
-      int level = 0;
-      for (;;) {
-        for (int j0 = 0; j0 < r.count; j0 += 64) {
-          // every lane loads (the index is clamped into the row) so that the load and its use stay
-          // in one block; lanes past the end of the row are discarded by `valid`
-          const bool valid = j0 + lane < r.count;
-          const int j = min(j0 + lane, r.count - 1);
-          ArcRec a = a0;
-          if (level != 0 || j0 != 0) a = t.arc[r.begin + j];
-          const int tk = a.token;
-          bool shadowed = !valid;
-          if (SEL == 2) shadowed = shadowed || tk == excl;
-          if (multi) {
-            if (level > 0) shadowed = shadowed || tag_test(tags, tk);  // a deeper chain state owns this token
-            if (valid) tag_set(tags, tk);
-          }
-          hit_vb = hit_vb || (valid && tk == vb);
-          const float fa = __fadd_rn(row[tk], __fmul_rn(alpha, __fadd_rn(p, a.score)));
-          if (!shadowed && (fa > bf || (fa == bf && tk < btok))) {
-            bf = fa;
-            btok = tk;
-            bchild = r.begin + j + 1;
+      // The first arcs of the chain head were requested at the start of the frame.  They are used
+      // here, outside the loop, so that the wait for them is a wait for them alone: inside the loop
+      // the compiler could not tell them from the arcs loaded there and would wait for every load in
+      // flight, the prefetched rows included.
+#pragma unroll
+      for (int q = 0; q < kEarly; ++q) {
+        if (q == 0 || 64 * q < r.count)
+          eval(early[q], 64 * q + lane < r.count, r.begin + max(0, min(64 * q + lane, r.count - 1)) + 1, p, 0);
+      }
+      for (int level = 0;; ++level) {
+        // Further arcs, up to four batches at a time so that their latencies overlap.  Every lane loads (the
+        // index is clamped into the row) so that the load and its use stay in one block; lanes past the
+        // end of the row are discarded by `valid`.
+        constexpr int kGroup = kEarly > 1 ? 4 : 1;
+        for (int j0 = (level == 0 ? 64 * kEarly : 0); j0 < r.count; j0 += 64 * kGroup) {
+          ArcRec more[kGroup];
+#pragma unroll
+          for (int q = 0; q < kGroup; ++q) more[q] = t.arc[r.begin + min(j0 + 64 * q + lane, r.count - 1)];
+#pragma unroll
+          for (int q = 0; q < kGroup; ++q) {
+            if (q == 0 || j0 + 64 * q < r.count)
+              eval(more[q], j0 + 64 * q + lane < r.count, r.begin + min(j0 + 64 * q + lane, r.count - 1) + 1, p, level);
           }
         }
         p = __fadd_rn(p, r.backoff);
         if (r.fail == 0) break;
         r = nrec;
         if (r.fail != 0) nrec = load_rec(t, r.fail);
-        ++level;
       }
     }
 
@@ -484,6 +506,9 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
   const int V = t.V;
   const float* rp = logp + static_cast<size_t>(b) * row_stride + static_cast<size_t>(f0) * frame_stride;
   constexpr int NB = COMPARE ? 2 : 3;  // ring size: a re-run is short, one row ahead is enough there
+  // Batches of 64 arcs requested at the start of a frame: 256 arcs cover all but a few states; the two-stage
+  // rules hold more state in registers and take half of that, a re-run (16 waves per workgroup) one batch.
+  constexpr int kEarlyBatches = COMPARE ? 1 : (SEL == 0 ? 4 : 2);
   float xb[NB][16], c[16];
   load16<FULL>(rp, 0, V, lane, -INFINITY, xb[0]);
   if (NB == 3 && f0 + 1 < f1) load16<FULL>(rp + frame_stride, 0, V, lane, -INFINITY, xb[1]);
@@ -515,47 +540,64 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
     }
   };
   size_t o = static_cast<size_t>(f0) * B + b;
-  for (int fb = f0; fb < f1; fb += NB) {
-#pragma unroll
-    for (int u = 0; u < NB; ++u) {
-      const int f = fb + u;
-      if (f < f1) {
-        const bool more = f + NB - 1 < f1;
-        const float* rpn = rp + (NB - 1) * frame_stride;
-        float val;
-        int tok;
-        frame_1k<FULL, SEL>(t, cur, xb[u], c, c_p, alpha, row, tags, lane, last, f + 1 < f1,
-                            [&]() { if (more) load16<FULL>(rpn, 0, V, lane, -INFINITY, xb[(u + NB - 1) % NB]); }, val,
-                            tok);
-        if (!DEFER) {
-          int stored = -1, stored_tok = tok;
-          if (COMPARE) {
-            stored = uniform_i(__hip_atomic_load(states + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-            if (SEL == 2) stored_tok = uniform_i(__hip_atomic_load(tokens + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-          }
-          if (lane == 0) {
-            tokens[o] = tok;
-            states[o] = cur.s;
-            scores[o] = val;
-          }
-          if (COMPARE && stored == cur.s && stored_tok == tok) return;
-          o += B;
-        } else {
-          const int slot = f - base;
-          if (lane == slot) {
-            o_tok = tok;
-            o_st = cur.s;
-            o_sc = val;
-          }
-          if (slot == 63) {
-            flush(64);
-            base = f + 1;
-          }
-        }
-        if (SEL == 2) last = tok;
-        rp += frame_stride;
+  // One frame with its row in ring slot U.  STEADY frames request the row NB-1 frames ahead without a
+  // condition (the last frames of the range ask for the last row again): only then can the compiler
+  // count the loads issued after the arcs and after the current row, and wait for exactly those instead of
+  // for everything in flight.  Returns true when a re-run has met the stored trajectory.
+  auto do_frame = [&](auto slot_c, auto steady_c, int f) -> bool {
+    constexpr int U = decltype(slot_c)::value;
+    constexpr bool STEADY = decltype(steady_c)::value;
+    const int ahead = min(f + NB - 1, f1 - 1) - f;  // frames between this one and the row requested now
+    const float* rpn = rp + static_cast<int64_t>(ahead) * frame_stride;
+    const bool more = f + NB - 1 < f1;
+    float val;
+    int tok;
+    frame_1k<FULL, SEL, kEarlyBatches>(t, cur, xb[U], c, c_p, alpha, row, tags, lane, last, f + 1 < f1,
+                        [&]() {
+                          if (STEADY || more) load16<FULL>(rpn, 0, V, lane, -INFINITY, xb[(U + NB - 1) % NB]);
+                        },
+                        val, tok);
+    if (!DEFER) {
+      int stored = -1, stored_tok = tok;
+      if (COMPARE) {
+        stored = uniform_i(__hip_atomic_load(states + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        if (SEL == 2) stored_tok = uniform_i(__hip_atomic_load(tokens + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+      }
+      if (lane == 0) {
+        tokens[o] = tok;
+        states[o] = cur.s;
+        scores[o] = val;
+      }
+      if (COMPARE && stored == cur.s && stored_tok == tok) return true;
+      o += B;
+    } else {
+      const int slot = f - base;
+      if (lane == slot) {
+        o_tok = tok;
+        o_st = cur.s;
+        o_sc = val;
+      }
+      if (slot == 63) {
+        flush(64);
+        base = f + 1;
       }
     }
+    if (SEL == 2) last = tok;
+    rp += frame_stride;
+    return false;
+  };
+  using std::integral_constant;
+  int fb = f0;
+  for (; fb + NB <= f1; fb += NB) {  // whole turns of the ring: straight-line code
+    if (do_frame(integral_constant<int, 0>{}, integral_constant<bool, true>{}, fb)) return;
+    if (do_frame(integral_constant<int, 1>{}, integral_constant<bool, true>{}, fb + 1)) return;
+    if constexpr (NB == 3) {
+      if (do_frame(integral_constant<int, 2>{}, integral_constant<bool, true>{}, fb + 2)) return;
+    }
+  }
+  if (fb < f1 && do_frame(integral_constant<int, 0>{}, integral_constant<bool, false>{}, fb)) return;
+  if constexpr (NB == 3) {
+    if (fb + 1 < f1 && do_frame(integral_constant<int, 1>{}, integral_constant<bool, false>{}, fb + 1)) return;
   }
   if (DEFER) flush(f1 - base);
 }
