@@ -475,3 +475,24 @@ def test_fuse_frames_extreme_shapes(T, B):
         torch.cuda.synchronize()
         assert np.array_equal(d_tok.cpu().numpy(), want[0]) and np.array_equal(d_st.cpu().numpy(), want[1])
         assert_scores(d_sc.cpu().numpy(), want[2])
+
+
+def test_root_only_tree_is_plain_argmax_in_every_fused_call():
+    """No phrases at all: one state, no arcs (the kernels' clamped arc reads then touch the dense root row)."""
+    V, B, T = 1024, 9, 40
+    empty_t, empty_o = np.zeros(0, np.int32), np.zeros(1, np.int64)
+    ot, tr = build_both(empty_t, empty_o, V, 0, unk_score=0.5)
+    logp = W.make_logp(W.CONFIGS[2], steps=T, batch=B)
+    want = ot.fuse_frames(logp, np.zeros(B, np.int32), 0.7)
+    got = gpu_fuse_frames(tr, dev(logp), dev(np.zeros(B, np.int32)), 0.7)
+    assert np.array_equal(got[0], want[0]) and np.all(got[1] == 0)
+    assert_scores(got[2], want[2])
+    tk, st, sc = gpu_fuse_step(tr, dev(logp[0]), dev(np.zeros(B, np.int32)), 0.7)
+    torch.cuda.synchronize()
+    assert np.array_equal(tk.cpu().numpy(), want[0][0])
+    hyp = np.zeros(8, np.float32)
+    wb = ot.fuse_step_beam(logp[0][:8], hyp, np.zeros(8, np.int32), 0.7, 2, 4)
+    gb = gpu_beam_step(tr, dev(logp[0][:8]), dev(hyp), dev(np.zeros(8, np.int32)), 0.7, 2, 4)
+    torch.cuda.synchronize()
+    for g, w in zip(gb[:3], wb[:3]):
+        assert np.array_equal(g.cpu().numpy(), w)
