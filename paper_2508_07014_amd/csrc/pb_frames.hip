@@ -399,8 +399,15 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
     float base_val = M;
     int base_tok = vb;
     const bool mine0 = btok != INT_MAX;
+    // Most frames end here: the best arc stays below the base winner and does not shadow it.
+    bool contest = false;
+    bool vb_overridden = false;
     if (__ballot(mine0) != 0) {
       MA = ukey_val(wave_max_u(mine0 ? ukey(bf) : 0u));
+      vb_overridden = __ballot(hit_vb) != 0;
+      contest = vb_overridden || MA >= M;
+    }
+    if (contest) {
       const bool mine = mine0 && bf == MA;
       const u64 eq = __ballot(mine);
       if ((eq & (eq - 1)) == 0) {  // one lane holds the maximum
@@ -411,7 +418,6 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
         va = wave_min_nn(mine ? btok : INT_MAX);
         achild = __builtin_amdgcn_readlane(bchild, first_lane(__ballot(mine && btok == va)));
       }
-      const bool vb_overridden = __ballot(hit_vb) != 0;
       if (MA > M) {
         arc_wins = true;
       } else if (!vb_overridden) {
