@@ -486,6 +486,29 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
   out_val = uniform_f(out_val);
 }
 
+// Segment boundaries of the multi-frame decoder (single-stage rule).  A segment that does not begin the
+// call starts from a guess instead of the root: the state the frame before it leads to when its base
+// winner under root-state boosts is taken -- which is what the true decode does in most frames.  The
+// segment that ends there computes the same guess from the same row, compares it with its actual end
+// state and, if they agree, sets kGuessOk in the state word it stores for its last frame; the fix-up pass
+// then has nothing to re-run for the next segment, and clears the bit.  States stay below 2^30 for this.
+constexpr int kGuessOk = 1 << 30;
+
+template <bool FULL>
+__device__ __forceinline__ int guess_state(const TreeView& t, const float (&x)[16], const float (&c0)[16], int lane) {
+  float f[16], g[4];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) f[j] = __fadd_rn(x[j], c0[j]);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) g[i] = max4(f[4 * i], f[4 * i + 1], f[4 * i + 2], f[4 * i + 3]);
+  const float M = ukey_val(wave_max_u(ukey(max4(g[0], g[1], g[2], g[3]))));
+  const int v = uniform_i(first_token_equal(f, g, M, lane));
+  return v == t.blank ? 0 : uniform_i(t.root_next[v]);  // a blank keeps a state nobody knows here: the root
+}
+
+// State word of a stored frame without the boundary bit (an invalid frame holds -1 and stays as it is).
+__device__ __forceinline__ int plain_state(int word) { return word < 0 ? word : (word & ~kGuessOk); }
+
 __device__ __forceinline__ void fill_invalid(int B, int b, int f0, int f1, int32_t* tokens, int32_t* states,
                                              float* scores, int lane) {
   for (int f = f0 + lane; f < f1; f += 64) {
@@ -503,12 +526,17 @@ __device__ __forceinline__ void fill_invalid(int B, int b, int f0, int f1, int32
 // the CTC rule where the label feeds the next frame, the token in `tokens` (the stored trajectory is
 // then valid from there on).
 //   Rows travel through a ring of register buffers: the frame in hand and the one or two after it.
-template <bool COMPARE, bool FULL, int SEL>
+//   EDGE (pass 1 of the multi-frame decoder, single-stage rule): the range starts from a guess when it
+//   does not begin the call (f0 > 0) and marks its last state word when its own guess for the next
+//   range (f1 < T) turns out right.
+template <bool COMPARE, bool FULL, int SEL, bool EDGE>
 __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
                                               int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s_in,
-                                              int last_in, int32_t* __restrict__ tokens, int32_t* __restrict__ states,
-                                              float* __restrict__ scores, float* row, unsigned* tags, int lane) {
+                                              int last_in, int T, int32_t* __restrict__ tokens,
+                                              int32_t* __restrict__ states, float* __restrict__ scores, float* row,
+                                              unsigned* tags, int lane) {
   if (f0 >= f1) return;
+  constexpr bool GUESS = EDGE && !COMPARE && SEL == 0;
   const int V = t.V;
   const float* rp = logp + static_cast<size_t>(b) * row_stride + static_cast<size_t>(f0) * frame_stride;
   constexpr int NB = COMPARE ? 2 : 3;  // ring size: a re-run is short, one row ahead is enough there
@@ -519,7 +547,14 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
   load16<FULL>(rp, 0, V, lane, -INFINITY, xb[0]);
   if (NB == 3 && f0 + 1 < f1) load16<FULL>(rp + frame_stride, 0, V, lane, -INFINITY, xb[1]);
   load16<FULL>(t.root_score, 0, V, lane, 0.0f, c);  // needs no state: requested before the state is looked at
-  const int s = uniform_i(s_in);
+  int s = uniform_i(s_in);
+  const bool guessable = GUESS && t.num_states < kGuessOk;
+  if (guessable && f0 > 0 && s == 0) {  // (an invalid start state, e.g. of an unknown tree, is left as it is)
+    float xw[16], c0[16];
+    load16<FULL>(rp - frame_stride, 0, V, lane, -INFINITY, xw);
+    make_base_boost<SEL>(0, lane, t.blank, 0.0f, alpha, c, c0);
+    s = guess_state<FULL>(t, xw, c0, lane);
+  }
   int last = -1;
   if (SEL == 2) last = uniform_i(last_in);
   if (!valid_state(t, s)) {
@@ -563,15 +598,21 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
                           if (STEADY || more) load16<FULL>(rpn, 0, V, lane, -INFINITY, xb[(U + NB - 1) % NB]);
                         },
                         val, tok);
+    int word = cur.s;  // what is stored for the frame's state
+    if (guessable && f + 1 == f1 && f1 < T) {
+      float c0[16];
+      rebuild_base_boost<FULL, SEL>(t, lane, 0.0f, alpha, c0);
+      if (guess_state<FULL>(t, xb[U], c0, lane) == cur.s) word |= kGuessOk;
+    }
     if (!DEFER) {
       int stored = -1, stored_tok = tok;
       if (COMPARE) {
-        stored = uniform_i(__hip_atomic_load(states + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        stored = plain_state(uniform_i(__hip_atomic_load(states + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)));
         if (SEL == 2) stored_tok = uniform_i(__hip_atomic_load(tokens + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
       }
       if (lane == 0) {
         tokens[o] = tok;
-        states[o] = cur.s;
+        states[o] = word;
         scores[o] = val;
       }
       if (COMPARE && stored == cur.s && stored_tok == tok) return true;
@@ -580,7 +621,7 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
       const int slot = f - base;
       if (lane == slot) {
         o_tok = tok;
-        o_st = cur.s;
+        o_st = word;
         o_sc = val;
       }
       if (slot == 63) {
@@ -796,17 +837,17 @@ __device__ __forceinline__ void run_frames_multi(const TreeView& t, const float*
 }
 
 // MODE 0: V == 1024, 1: V < 1024, 2: V > 1024 (multi-chunk).
-template <bool COMPARE, int MODE, int SEL>
+template <bool COMPARE, int MODE, int SEL, bool EDGE = false>
 __device__ __forceinline__ void run_frames(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
                                            int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s, int last,
-                                           int32_t* __restrict__ tokens, int32_t* __restrict__ states,
+                                           int T, int32_t* __restrict__ tokens, int32_t* __restrict__ states,
                                            float* __restrict__ scores, float* row, unsigned* tags, int lane) {
   if constexpr (MODE == 0)
-    run_frames_1k<COMPARE, true, SEL>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, tokens, states,
-                                      scores, row, tags, lane);
+    run_frames_1k<COMPARE, true, SEL, EDGE>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, T, tokens,
+                                            states, scores, row, tags, lane);
   else if constexpr (MODE == 1)
-    run_frames_1k<COMPARE, false, SEL>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, tokens, states,
-                                       scores, row, tags, lane);
+    run_frames_1k<COMPARE, false, SEL, EDGE>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, T, tokens,
+                                             states, scores, row, tags, lane);
   else
     run_frames_multi<COMPARE, SEL>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, tokens, states,
                                    scores, row, tags, lane);
@@ -844,8 +885,8 @@ __global__ void __launch_bounds__(256, 4) frames_spec_kernel(DeviceTree dt, Tree
     if (SEL == 2 && last0 != nullptr) last = last0[b];
   }
   if (!tree_ok) s = -1;  // an unknown tree marks every frame of the hypothesis like an invalid state
-  run_frames<false, MODE, SEL>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, tokens, states, scores,
-                               row, tags, lane);
+  run_frames<false, MODE, SEL, true>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, T, tokens, states,
+                                     scores, row, tags, lane);
 }
 
 // Pass 2: one workgroup per hypothesis; its waves share the segments j = 1 .. nseg-1.
@@ -872,10 +913,10 @@ __global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, TreePic
   const TreeView t = make_view(mine);
   auto rerun = [&](int seg, int s, int last) {
     const int f0 = seg * seg_len, f1 = min(T, f0 + seg_len);
-    run_frames<true, MODE, SEL>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, tokens, states, scores,
+    run_frames<true, MODE, SEL>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, T, tokens, states, scores,
                                 row, tags, lane);
   };
-  auto end_state_of = [&](int seg) {  // state after the last frame of segment `seg`
+  auto end_word_of = [&](int seg) {  // state word of the last frame of segment `seg` (boundary bit included)
     const int32_t* p = states + static_cast<size_t>((seg + 1) * seg_len - 1) * B + b;
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   };
@@ -886,12 +927,15 @@ __global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, TreePic
   };
   for (int seg = 1 + wave; seg < nseg; seg += nwaves) {
     // consumed inside rerun, after its row loads are on their way
-    const int s = end_state_of(seg - 1), last = end_token_of(seg - 1);
+    const int word = end_word_of(seg - 1), last = end_token_of(seg - 1);
+    const int s = plain_state(word);
     if (lane == 0) {
       assumed[seg] = s;
       assumed_tok[seg] = last;
     }
-    rerun(seg, s, last);  // pass 1 assumed the root: a segment whose neighbour ended there meets at once
+    // pass 1 started the segment from a guess; where its neighbour has found the guess right there is
+    // nothing to do, elsewhere the segment is re-run until it meets what is stored
+    if (uniform_i(word) < 0 || (uniform_i(word) & kGuessOk) == 0) rerun(seg, s, last);
   }
   // (b) rounds: wave 0 compares the outcome at the end of every segment j-1 with what segment j was last
   // re-run from and publishes the set of stale segments; the waves re-run those in parallel from the
@@ -902,7 +946,7 @@ __global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, TreePic
     __syncthreads();
     if (wave == 0) {
       const bool check = lane >= 1 && lane < nseg;
-      const int have = check ? end_state_of(lane - 1) : 0;
+      const int have = check ? plain_state(end_word_of(lane - 1)) : 0;
       const int have_tok = check ? end_token_of(lane - 1) : 0;
       const bool stale = check && (have != assumed[lane] || (SEL == 2 && have_tok != assumed_tok[lane]));
       if (stale) {
@@ -923,6 +967,12 @@ __global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, TreePic
       bad &= bad - 1;
       if (k % nwaves == wave) rerun(seg, assumed[seg], assumed_tok[seg]);
     }
+  }
+  // every re-run is done: the boundary bits of pass 1 leave the output
+  if (wave == 0 && lane < nseg - 1) {
+    int32_t* p = states + static_cast<size_t>((lane + 1) * seg_len - 1) * B + b;
+    const int word = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (word >= 0 && (word & kGuessOk) != 0) *p = word & ~kGuessOk;
   }
 }
 
@@ -945,8 +995,8 @@ __global__ void __launch_bounds__(256) step_wave_kernel(DeviceTree dt, TreePick 
   const int s = tree_ok ? states_in[b] : -1;  // an unknown tree marks the hypothesis like an invalid state
   int last = -1;
   if (SEL == 2 && last_in != nullptr) last = last_in[b];
-  run_frames<false, MODE, SEL>(t, logp, 0, row_stride, alpha, B, b, 0, 1, s, last, tokens, states_out, scores, row, tags,
-                               lane);
+  run_frames<false, MODE, SEL>(t, logp, 0, row_stride, alpha, B, b, 0, 1, s, last, 1, tokens, states_out, scores, row,
+                               tags, lane);
 }
 
 // ------------------------------------------------------------------------------------------------
