@@ -486,16 +486,31 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
   out_val = uniform_f(out_val);
 }
 
-// Segment boundaries of the multi-frame decoder (single-stage rule).  A segment that does not begin the
+// Segment boundaries of the multi-frame decoder.  A segment that does not begin the
 // call starts from a guess instead of the root: the state the frame before it leads to when its base
 // winner under root-state boosts is taken -- which is what the true decode does in most frames.  The
 // segment that ends there computes the same guess from the same row, compares it with its actual end
-// state and, if they agree, sets kGuessOk in the state word it stores for its last frame; the fix-up pass
+// state (under the CTC rule also with its last label) and, if they agree, sets kGuessOk in the state
+// word it stores for its last frame; the fix-up pass
 // then has nothing to re-run for the next segment, and clears the bit.  States stay below 2^30 for this.
 constexpr int kGuessOk = 1 << 30;
 
-template <bool FULL>
-__device__ __forceinline__ int guess_state(const TreeView& t, const float (&x)[16], const float (&c0)[16], int lane) {
+// c0: the base boosts of the root state for the rule (make_base_boost<SEL> with p_root = 0).  Under the
+// two-stage rules a frame whose raw arg-max is the blank keeps a state nobody knows here: the guess is
+// then the root, and mostly wrong.
+template <bool FULL, int SEL>
+__device__ __forceinline__ void guess_state(const TreeView& t, const float (&x)[16], const float (&c0)[16], int lane,
+                                            int& state, int& label) {
+  if constexpr (SEL != 0) {
+    float M0;
+    int v0;
+    plain_argmax(x, lane, M0, v0);
+    if (v0 == t.blank) {
+      state = 0;
+      label = uniform_i(v0);
+      return;
+    }
+  }
   float f[16], g[4];
 #pragma unroll
   for (int j = 0; j < 16; ++j) f[j] = __fadd_rn(x[j], c0[j]);
@@ -503,7 +518,8 @@ __device__ __forceinline__ int guess_state(const TreeView& t, const float (&x)[1
   for (int i = 0; i < 4; ++i) g[i] = max4(f[4 * i], f[4 * i + 1], f[4 * i + 2], f[4 * i + 3]);
   const float M = ukey_val(wave_max_u(ukey(max4(g[0], g[1], g[2], g[3]))));
   const int v = uniform_i(first_token_equal(f, g, M, lane));
-  return v == t.blank ? 0 : uniform_i(t.root_next[v]);  // a blank keeps a state nobody knows here: the root
+  label = v;
+  state = v == t.blank ? 0 : uniform_i(t.root_next[v]);  // (single-stage rule: a blank keeps an unknown state)
 }
 
 // State word of a stored frame without the boundary bit (an invalid frame holds -1 and stays as it is).
@@ -536,7 +552,7 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
                                               int32_t* __restrict__ states, float* __restrict__ scores, float* row,
                                               unsigned* tags, int lane) {
   if (f0 >= f1) return;
-  constexpr bool GUESS = EDGE && !COMPARE && SEL == 0;
+  constexpr bool GUESS = EDGE && !COMPARE;
   const int V = t.V;
   const float* rp = logp + static_cast<size_t>(b) * row_stride + static_cast<size_t>(f0) * frame_stride;
   constexpr int NB = COMPARE ? 2 : 3;  // ring size: a re-run is short, one row ahead is enough there
@@ -548,15 +564,17 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
   if (NB == 3 && f0 + 1 < f1) load16<FULL>(rp + frame_stride, 0, V, lane, -INFINITY, xb[1]);
   load16<FULL>(t.root_score, 0, V, lane, 0.0f, c);  // needs no state: requested before the state is looked at
   int s = uniform_i(s_in);
+  int last = -1;
+  if (SEL == 2) last = uniform_i(last_in);
   const bool guessable = GUESS && t.num_states < kGuessOk;
   if (guessable && f0 > 0 && s == 0) {  // (an invalid start state, e.g. of an unknown tree, is left as it is)
     float xw[16], c0[16];
     load16<FULL>(rp - frame_stride, 0, V, lane, -INFINITY, xw);
     make_base_boost<SEL>(0, lane, t.blank, 0.0f, alpha, c, c0);
-    s = guess_state<FULL>(t, xw, c0, lane);
+    int label;
+    guess_state<FULL, SEL>(t, xw, c0, lane, s, label);
+    if (SEL == 2) last = label;
   }
-  int last = -1;
-  if (SEL == 2) last = uniform_i(last_in);
   if (!valid_state(t, s)) {
     fill_invalid(B, b, f0, f1, tokens, states, scores, lane);
     return;
@@ -598,12 +616,7 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
                           if (STEADY || more) load16<FULL>(rpn, 0, V, lane, -INFINITY, xb[(U + NB - 1) % NB]);
                         },
                         val, tok);
-    int word = cur.s;  // what is stored for the frame's state
-    if (guessable && f + 1 == f1 && f1 < T) {
-      float c0[16];
-      rebuild_base_boost<FULL, SEL>(t, lane, 0.0f, alpha, c0);
-      if (guess_state<FULL>(t, xb[U], c0, lane) == cur.s) word |= kGuessOk;
-    }
+    const int word = cur.s;
     if (!DEFER) {
       int stored = -1, stored_tok = tok;
       if (COMPARE) {
@@ -645,6 +658,22 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
   if (fb < f1 && do_frame(integral_constant<int, 0>{}, integral_constant<bool, false>{}, fb)) return;
   if constexpr (NB == 3) {
     if (fb + 1 < f1 && do_frame(integral_constant<int, 1>{}, integral_constant<bool, false>{}, fb + 1)) return;
+  }
+  if (guessable && f1 < T) {
+    // The guess the next range starts from, made here from the same row (read again: it was the last
+    // one this wave loaded); if it is what this range really ends in, the last state word says so.
+    float xl[16], c0[16];
+    load16<FULL>(rp - frame_stride, 0, V, lane, -INFINITY, xl);
+    rebuild_base_boost<FULL, SEL>(t, opaque(lane), 0.0f, alpha, c0);
+    int g, glabel;
+    guess_state<FULL, SEL>(t, xl, c0, lane, g, glabel);
+    if (g == cur.s && (SEL != 2 || glabel == last)) {
+      if (DEFER) {
+        if (lane == f1 - 1 - base) o_st |= kGuessOk;
+      } else if (lane == 0) {
+        states[static_cast<size_t>(f1 - 1) * B + b] = cur.s | kGuessOk;
+      }
+    }
   }
   if (DEFER) flush(f1 - base);
 }
