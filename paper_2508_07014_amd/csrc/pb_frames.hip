@@ -23,13 +23,14 @@
 //  * The record of the next state (arc range, failure link, backoffs) is fetched with the lookup
 //    that yields the state: a dense per-token table holds it for the base winner and is read as
 //    soon as that winner is known, before the arcs have been evaluated.
-//  * Multi-frame decoding splits the T frames of a hypothesis into segments decoded concurrently,
-//    every segment but the first speculatively from the root state.  The decoder is a finite
-//    automaton step, so a re-run from the true start state needs to go only as far as the frame
-//    where its state meets the speculative trajectory; a second kernel does these short re-runs
-//    (all segments in parallel, from the neighbouring segment's end state) and then compares the
-//    assumed start states with the final ones, re-running the stale segments in parallel rounds.
-//    The result is identical to T sequential steps.
+//  * Multi-frame decoding splits the T frames of a hypothesis into segments decoded concurrently.  A
+//    segment that does not begin the call starts from a guess: the state the base winner of the frame
+//    before it leads to (right in most frames).  The decoder is a finite automaton step, so a re-run
+//    from the true start state needs to go only as far as the frame where it meets the stored
+//    trajectory.  The segment on the left certifies a right guess with a bit in its last state word;
+//    a second kernel re-runs the other segments (in parallel, from the neighbouring segment's end
+//    state), then compares the assumed start states with the final ones, re-running stale segments in
+//    parallel rounds, and clears the bits.  The result is identical to T sequential steps.
 //  * Selection rules (Sec. II-C).  The two-stage rules first take the arg-max of the raw row; a blank
 //    (or, for CTC, a repeat of the previous label) ends the frame there.  Tokens barred from the
 //    boosted re-selection are NaN in the candidate registers, which no maximum and no equality test
@@ -281,7 +282,8 @@ __device__ __forceinline__ void rebuild_base_boost(const TreeView& t, int lane, 
 template <bool FULL, int SEL, int EARLY, typename NextRow>
 __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const float (&x)[16], float (&c)[16],
                                          float& c_p, float alpha, float* row, unsigned* tags, int lane, int last,
-                                         bool need_record, NextRow&& next_row, float& out_val, int& out_tok) {
+                                         bool need_record, NextRow&& next_row, float& out_val, int& out_tok,
+                                         bool& row_in_lds) {
   const int s = cur.s;
   const Rec rec0 = cur.rec;
   const bool chain = (s != 0);
@@ -306,6 +308,7 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
     if (v0 == t.blank || (SEL == 2 && v0 == last)) {
       out_val = uniform_f(M0);
       out_tok = uniform_i(v0);
+      row_in_lds = false;
       return;
     }
   }
@@ -317,6 +320,7 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
 #pragma unroll
   for (int j = 0; j < 16; ++j) f[j] = __fadd_rn(x[j], c[j]);
   if (chain) store_row_lds(row, lane, x);
+  row_in_lds = chain;
   const Cursor start = cur;
   // The CTC rule bars the previous label from the re-selection.  The frame is first decided with the
   // label still in; only if it wins is the frame decided again with the label excluded (excl >= 0).
@@ -599,6 +603,7 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
     }
   };
   size_t o = static_cast<size_t>(f0) * B + b;
+  bool row_in_lds = false;  // the LDS row holds the raw row of the frame decoded last
   // One frame with its row in ring slot U.  STEADY frames request the row NB-1 frames ahead without a
   // condition (the last frames of the range ask for the last row again): only then can the compiler
   // count the loads issued after the arcs and after the current row, and wait for exactly those instead of
@@ -615,7 +620,7 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
                         [&]() {
                           if (STEADY || more) load16<FULL>(rpn, 0, V, lane, -INFINITY, xb[(U + NB - 1) % NB]);
                         },
-                        val, tok);
+                        val, tok, row_in_lds);
     const int word = cur.s;
     if (!DEFER) {
       int stored = -1, stored_tok = tok;
@@ -660,10 +665,18 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
     if (fb + 1 < f1 && do_frame(integral_constant<int, 1>{}, integral_constant<bool, false>{}, fb + 1)) return;
   }
   if (guessable && f1 < T) {
-    // The guess the next range starts from, made here from the same row (read again: it was the last
-    // one this wave loaded); if it is what this range really ends in, the last state word says so.
+    // The guess the next range starts from, made here from the same row; if it is what this range really
+    // ends in, the last state word says so.
     float xl[16], c0[16];
-    load16<FULL>(rp - frame_stride, 0, V, lane, -INFINITY, xl);
+    if (row_in_lds) {  // the usual case: the last frame left its raw row in LDS
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float4 q = *reinterpret_cast<const float4*>(row + 256 * i + 4 * lane);
+        xl[4 * i + 0] = q.x; xl[4 * i + 1] = q.y; xl[4 * i + 2] = q.z; xl[4 * i + 3] = q.w;
+      }
+    } else {
+      load16<FULL>(rp - frame_stride, 0, V, lane, -INFINITY, xl);
+    }
     rebuild_base_boost<FULL, SEL>(t, opaque(lane), 0.0f, alpha, c0);
     int g, glabel;
     guess_state<FULL, SEL>(t, xl, c0, lane, g, glabel);
