@@ -1131,10 +1131,10 @@ __global__ void __launch_bounds__(64 * kBeamWaveMaxK) beam_wave_kernel(
     const int v = uniform_i(first_token_equal(tv, g, M, lane));
     int nx = s;  // the blank keeps the state
     if (v != t.blank) nx = tag_test(tags, v) ? ov_next[v] : t.root_next[v];
-    if (lane == 0) {
-      cand_val[wave * K + r] = M;
-      cand_idx[wave * K + r] = wave * V + v;
-      cand_nxt[wave * K + r] = nx;
+    if (lane == 0) {  // `rounds` entries per wave, packed
+      cand_val[wave * rounds + r] = M;
+      cand_idx[wave * rounds + r] = wave * V + v;
+      cand_nxt[wave * rounds + r] = nx;
     }
     const int ln = opaque(lane);
 #pragma unroll

@@ -70,3 +70,45 @@ def test_frames_random_cases(chunk):
             for b in bad:
                 assert np.all(tk[:, b] == -1) and np.all(st[:, b] == -1) and np.all(np.isnan(sc[:, b])), where
         pb.pb_free(tr)
+
+
+@pytest.mark.parametrize("chunk", range(4))
+def test_beam_step_random_cases(chunk):
+    """Beam widths on both kernels (K <= 8 wave-per-beam, wider ones per workgroup), K above V, exact ties,
+    dead beams, blank ids other than 0."""
+    rng = np.random.default_rng(777 + chunk)
+    for case in range(40):
+        V = int(rng.choice([4, 8, 64, 128, 1024, 130, 2048]))
+        blank = int(rng.choice([0, -1, 2]))
+        cfg = W.Config(9, "fuzz", V, blank, int(rng.integers(1, 300)), 1, int(rng.integers(2, 7)), "zipf", 1.1, 1, 1, 1, 2.0)
+        toks, offs = W.make_phrases(cfg, seed=int(rng.integers(1 << 30)))
+        if blank >= 1:
+            toks = np.where(toks == blank, (blank + 1) % V or 1, toks).astype(np.int32)
+        wmode = int(rng.integers(0, 3))
+        ot = OracleTree(toks, offs, V, blank, weight_mode=wmode)
+        tr = pb.pb_build(toks, offs, V, blank, weight_mode=wmode, device=0)
+        K, U = int(rng.choice([1, 2, 3, 4, 5, 8, 9, 16])), int(rng.choice([1, 3, 10]))
+        states = rng.integers(0, ot.num_states, U * K).astype(np.int32)
+        kind = int(rng.integers(0, 3))
+        if kind == 0:
+            logp = W.log_softmax_rows(rng.standard_normal((U * K, V)) * 2)
+        elif kind == 1:
+            logp = np.round(rng.standard_normal((U * K, V)) * 2).astype(np.float32)      # many exact ties
+        else:
+            logp = np.full((U * K, V), -3.0, np.float32)
+        hyp = rng.standard_normal(U * K).astype(np.float32)
+        if rng.random() < 0.5:
+            hyp[rng.integers(0, U * K, max(1, U * K // 3))] = -np.inf
+        if kind == 1:
+            hyp = np.round(hyp).astype(np.float32)
+        alpha = float(rng.choice([0.0, 0.5, 1.0]))
+        want = ot.fuse_step_beam(logp, hyp, states, alpha, U, K)
+        o = [torch.zeros(U * K, dtype=torch.int32, device=DEV) for _ in range(3)] + [torch.zeros(U * K, device=DEV)]
+        pb.pb_fuse_step_beam(tr, dev(logp), V, dev(hyp), dev(states), alpha, U, K, o[0], o[1], o[2], o[3], 0)
+        torch.cuda.synchronize()
+        where = dict(chunk=chunk, case=case, V=V, blank=blank, K=K, U=U, kind=kind, alpha=alpha, wmode=wmode)
+        for g, w in zip(o[:3], want[:3]):
+            assert np.array_equal(g.cpu().numpy(), w), where
+        sc, fin = o[3].cpu().numpy(), np.isfinite(want[3])
+        assert np.array_equal(sc[~fin], want[3][~fin]) and np.allclose(sc[fin], want[3][fin], atol=1e-5, rtol=0), where
+        pb.pb_free(tr)
