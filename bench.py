@@ -275,6 +275,30 @@ def main() -> int:
             extra["graph_replay"]["empty_kernel_us_per_node"] = _events(torch, g0.replay, 5) * 1e3 / frames
         except Exception as e:  # the graph regime is a side measurement; say why it is missing
             extra["graph_replay"] = {"error": repr(e)}
+        # the single-step kernel at growing batch (config 3 tree): where it leaves the latency-bound regime
+        gen = torch.Generator(device=dev).manual_seed(7)
+        step_sweep = {}
+        for Bs in (1024, 4096, 16384, 65536):
+            lp = torch.log_softmax(torch.randn((Bs, V), device=dev, generator=gen) * cfg.sigma, dim=-1)
+            o_tok = torch.empty(Bs, dtype=torch.int32, device=dev)
+            o_st = torch.empty(Bs, dtype=torch.int32, device=dev)
+            o_sc = torch.empty(Bs, dtype=torch.float32, device=dev)
+            rec = {}
+            for kind in ("depth1_states", "uniform_states"):
+                if kind == "depth1_states":   # what a greedy trajectory sits in
+                    stn = (1 + np.arange(Bs) % info["root_degree"]).astype(np.int32)
+                else:
+                    stn = W.sample_states(info["num_states"], Bs, 300 + Bs)
+                d_stn = torch.from_numpy(stn).to(dev)
+                fn = lambda: pb.pb_fuse_step(tree, lp, V, d_stn, cfg.alpha, Bs, o_tok, o_st, o_sc, stream)
+                fn()
+                ms = _events(torch, fn, 20)
+                byts = Bs * (4 * V + 16)
+                rec[kind] = {"us": ms * 1e3, "GBps": byts / (ms * 1e-3) / 1e9,
+                             "frac_hbm": byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+            step_sweep[f"B{Bs}"] = rec
+            del lp
+        extra["pb_fuse_step_batch_sweep"] = step_sweep
         # dense rows: config 5 sweep (V = 8192, 20K phrases), states drawn from all states
         cfg5 = W.CONFIGS[5]
         t5, o5 = W.make_phrases(cfg5)
