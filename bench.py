@@ -148,8 +148,10 @@ def main() -> int:
         out["cpu_baseline"] = {"value": B * T / cpu_s, "unit": "hyp-frames/s", "cores": oracle_threads(),
                                "kind": "oracle", "sample": f"the whole workload: {T} frames x {B} hypotheses, "
                                f"{cpu_s:.2f} s wall"}
+        # tokens and states bit-exact; scores exact too (uniform weights and alpha = 0.5 make every boost dyadic)
         out["parity"] = bool(np.array_equal(d_tok.cpu().numpy(), want[0]) and
-                             np.array_equal(d_st.cpu().numpy(), want[1]))
+                             np.array_equal(d_st.cpu().numpy(), want[1]) and
+                             np.array_equal(d_sc.cpu().numpy(), want[2]))
         # the same oracle on one thread, on the first 100 frames
         from oracle import set_oracle_threads
         nthreads = oracle_threads()
@@ -220,7 +222,8 @@ def main() -> int:
                 if not args.no_cpu:
                     w = ot.fuse_frames_select(lp, np.zeros(B, np.int32), None, cfg.alpha, mode)
                     rec["parity"] = bool(np.array_equal(d_tok.cpu().numpy(), w[0]) and
-                                         np.array_equal(d_st.cpu().numpy(), w[1]))
+                                         np.array_equal(d_st.cpu().numpy(), w[1]) and
+                                         np.array_equal(d_sc.cpu().numpy(), w[2]))
                     rec["blank_frac"] = float(np.mean(w[0] == cfg.blank_id))
                     rec["depth_ge2_frac"] = float(np.mean(w[1] > info["root_degree"]))
                 results[name][mname] = rec
@@ -333,6 +336,61 @@ def main() -> int:
             "us": ms * 1e3, "scores_per_s": 1024 * cfg5.vocab_size / (ms * 1e-3), "GBps": byts / (ms * 1e-3) / 1e9,
             "frac_hbm": byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}}
         del lp5
+        # config 5 greedy decode (V = 8192, blank-free, B = 256, 200 steps): the per-step shape that moves 8 MiB
+        cfg5 = W.CONFIGS[5]
+        T5, B5, V5 = cfg5.steps, cfg5.batch, cfg5.vocab_size
+        logp5 = W.make_logp(cfg5)
+        d_lp5 = torch.from_numpy(logp5).to(dev)
+        z5 = torch.zeros(B5, dtype=torch.int32, device=dev)
+        o5_tok = torch.empty((T5, B5), dtype=torch.int32, device=dev)
+        o5_st = torch.empty((T5, B5), dtype=torch.int32, device=dev)
+        o5_sc = torch.empty((T5, B5), dtype=torch.float32, device=dev)
+        bytes5 = T5 * B5 * (4 * V5 + 12) + 4 * B5
+
+        def rate5(ms):
+            return {"ms": ms, "us_per_frame": ms * 1e3 / T5, "hyp_frames_per_s": B5 * T5 / (ms * 1e-3),
+                    "GBps": bytes5 / (ms * 1e-3) / 1e9, "frac_hbm": bytes5 / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+        c5 = {"workload": "config 5: greedy, 20000 phrases of 2-8 Zipf(1.1) tokens, V=8192, blank-free, alpha=0.5, "
+                          "B=256, 200 steps, N(0,3) log-softmax logits (1.6 GiB of log-probs, read once per decode)"}
+        fn = lambda: pb.pb_fuse_frames(tree5, d_lp5, B5 * V5, V5, z5, cfg5.alpha, T5, B5, o5_tok, o5_st, o5_sc, stream)
+        fn()
+        c5["pb_fuse_frames"] = rate5(_events(torch, fn, 5))
+        if not args.no_cpu:
+            ot5 = OracleTree(t5, o5, V5, cfg5.blank_id)
+            w5 = ot5.fuse_frames(logp5, np.zeros(B5, np.int32), cfg5.alpha)
+            c5["pb_fuse_frames"]["parity"] = bool(np.array_equal(o5_tok.cpu().numpy(), w5[0]) and
+                                                  np.array_equal(o5_st.cpu().numpy(), w5[1]) and
+                                                  np.array_equal(o5_sc.cpu().numpy(), w5[2]))
+
+        def per_launch5(sp):
+            prev = z5
+            for t in range(T5):
+                pb.pb_fuse_step(tree5, d_lp5[t], V5, prev, cfg5.alpha, B5, o5_tok[t], o5_st[t], o5_sc[t], sp)
+                prev = o5_st[t]
+
+        per_launch5(stream)
+        torch.cuda.synchronize()
+        c5["per_launch"] = rate5(_events(torch, lambda: per_launch5(stream), 3))
+        if not args.no_cpu:
+            c5["per_launch"]["parity"] = bool(np.array_equal(o5_tok.cpu().numpy(), w5[0]) and
+                                              np.array_equal(o5_st.cpu().numpy(), w5[1]) and
+                                              np.array_equal(o5_sc.cpu().numpy(), w5[2]))
+        try:
+            g5 = torch.cuda.CUDAGraph()
+            side5 = torch.cuda.Stream()
+            side5.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side5):
+                with torch.cuda.graph(g5, stream=side5):
+                    per_launch5(int(side5.cuda_stream))
+            torch.cuda.current_stream().wait_stream(side5)
+            g5.replay()
+            torch.cuda.synchronize()
+            c5["graph_replay"] = rate5(_events(torch, g5.replay, 5))
+        except Exception as e:
+            c5["graph_replay"] = {"error": repr(e)}
+        extra["config5_greedy"] = c5
+        del d_lp5, logp5
         # beam step: config 4 shape (32 utterances x 4 beams, 5K phrases)
         cfg4 = W.CONFIGS[4]
         t4, o4 = W.make_phrases(cfg4)
