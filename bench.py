@@ -38,6 +38,25 @@ def _events(torch, fn, reps):
     return start.elapsed_time(stop) / reps
 
 
+def _load_probe():
+    """The bench-only probe library (dependent-load latency); built beforehand like the product library."""
+    import ctypes as C
+
+    from paper_2508_07014_amd import build as B
+    if not os.path.exists(B.PROBE_LIB):
+        B.build_probe(force=True)
+    lib = C.CDLL(B.PROBE_LIB)
+    lib.pb_probe_chase.restype = C.c_int
+    lib.pb_probe_chase.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+
+    def chase(d_table, n, start, hops, d_out, stream):
+        rc = lib.pb_probe_chase(d_table.data_ptr(), n, start, hops, d_out.data_ptr(), stream or None)
+        if rc != 0:
+            raise RuntimeError(f"pb_probe_chase: {rc}")
+
+    return chase
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -177,7 +196,8 @@ def main() -> int:
         # launch starts at a fresh place of the cycle, so its lines are touched for the first time since
         # the preparation step: "L2" = small table read beforehand, "MALL" = 64 MiB table read beforehand,
         # "HBM" = 1 GiB table after 512 MiB of unrelated traffic.
-        chase = {}
+        chase = _load_probe()
+        lat = {}
         d_one = torch.zeros(1, dtype=torch.int32, device=dev)
         hops = 20000
         for label, n in (("L2_256KiB_table", 1 << 16), ("MALL_64MiB_table", 1 << 24), ("HBM_1GiB_table", 1 << 28)):
@@ -186,7 +206,7 @@ def main() -> int:
             table = np.empty(n, np.int32)
             table[order] = np.roll(order, -1)
             d_table = torch.from_numpy(table).to(dev)
-            pb.pb_diag_chase(d_table, n, 0, 10, d_one, stream)
+            chase(d_table, n, 0, 10, d_one, stream)
             if n <= (1 << 24):
                 d_table.sum()
             else:
@@ -196,10 +216,10 @@ def main() -> int:
             torch.cuda.synchronize()
             starts = [int(order[(k + 1) * (n // 4)]) for k in range(3)]
             it = iter(starts)
-            ms = _events(torch, lambda: pb.pb_diag_chase(d_table, n, next(it), hops, d_one, stream), 3)
-            chase[label] = {"ns_per_hop": ms * 1e6 / hops}
+            ms = _events(torch, lambda: chase(d_table, n, next(it), hops, d_one, stream), 3)
+            lat[label] = {"ns_per_hop": ms * 1e6 / hops}
             del d_table, table, order
-        extra["dependent_load_latency"] = chase
+        extra["dependent_load_latency"] = lat
         # structured variants of config 3 through the same entry point, under the three selection rules
         # (single-stage, two-stage, two-stage with the CTC repeat rule), each checked against the oracle
         variants = {"as_written": {}, "planted_20pct": dict(planting=W.Planting(toks, offs)),
@@ -271,7 +291,7 @@ def main() -> int:
             with torch.cuda.stream(side):
                 with torch.cuda.graph(g0, stream=side):
                     for t in range(frames):
-                        pb.pb_diag_chase(tiny, 4, 0, 0, d_one, int(side.cuda_stream))
+                        chase(tiny, 4, 0, 0, d_one, int(side.cuda_stream))
             torch.cuda.current_stream().wait_stream(side)
             g0.replay()
             torch.cuda.synchronize()

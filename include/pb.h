@@ -102,6 +102,11 @@ typedef struct {
   const double* acc;        /* [N]   accumulated score root -> state, double                            */
   const float* root_score;  /* [V]   dense root row: arc score or c_unk                                 */
   const int32_t* root_next; /* [V]   dense root row: depth-1 state or 0 (self-loop)                     */
+  const float* p_root;      /* [N]   backoff scores summed from the state down to the root, fp32, in the
+                                     order a query pays them                                            */
+  const float* eos_score;   /* [N]   boost of the EOS token in every state (Sec. II-C): the largest score of
+                                     the other tokens, the blank aside, plus the final weight of an
+                                     end-of-phrase state; NULL for a tree without an EOS rule            */
 } pb_host_view;
 
 /*
@@ -240,15 +245,17 @@ int pb_fuse_step_beam_forest(const pb_forest* forest, const float* d_logp, int64
                              int32_t* d_states_out, float* d_scores_out, void* hip_stream);
 
 /*
- * pb_diag_chase -- measurement aid, not part of the method: one GPU lane performs `hops` dependent
- * loads i = d_table[i] starting at i = start and writes the last index to *d_out.  Timed by the
- * caller (events on the stream), it gives the latency of one dependent access for a table of n
- * entries -- the floor under every per-step call, whose state -> arcs -> next-state recurrence is
- * such a chain.  d_table int32[n], every entry in [0, n) (the caller's responsibility: entries are
- * not checked on the device); asynchronous on `hip_stream`.  PB_EINVAL for null pointers, n <= 0 or
- * n >= 2^31, start outside [0, n), hops < 0.
+ * pb_validate -- debug aid (host-side, O(N + V)): bounds-checks every index the kernels follow in the compiled
+ * tree -- arc rows tile the arc table and stay inside it, tokens in [0, V) and strictly ascending per row, arc j
+ * leads to state j + 1 one level deeper, failure links lead to strictly shallower states, the root row points at
+ * depth-1 states on the right token, the packed records equal the flat arrays.  PB_OK, or PB_ERANGE at the first
+ * violation.  pb_build runs it by itself when the environment variable PB_DEBUG is set to anything but "0".
+ * pb_validate_states -- the same for a HOST array of n state ids: PB_ERANGE and *first_bad (may be NULL) = the
+ * first index whose id is outside [0, num_states).  (On the device an id outside the range never faults: see the
+ * conventions above.)
  */
-int pb_diag_chase(const int32_t* d_table, int64_t n, int32_t start, int32_t hops, int32_t* d_out, void* hip_stream);
+int pb_validate(const pb_tree* tree);
+int pb_validate_states(const pb_tree* tree, const int32_t* states, int64_t n, int64_t* first_bad);
 
 const char* pb_strerror(int code);
 

@@ -18,8 +18,9 @@ PB_W_UNIFORM, PB_W_LOGDEPTH, PB_W_UNIFORM_FINAL = 0, 1, 2
 PB_SELECT_FUSED, PB_SELECT_TWO_STAGE, PB_SELECT_TWO_STAGE_CTC = 0, 1, 2
 
 EXPORTS = ["pb_build", "pb_free", "pb_info", "pb_host_arrays", "pb_state_prefix", "pb_score", "pb_fuse_step",
-           "pb_fuse_frames", "pb_fuse_step_select", "pb_fuse_frames_select", "pb_fuse_step_beam", "pb_diag_chase", "pb_forest_build", "pb_forest_free", "pb_score_forest",
-           "pb_fuse_step_forest", "pb_fuse_frames_forest", "pb_fuse_step_beam_forest", "pb_strerror"]
+           "pb_fuse_frames", "pb_fuse_step_select", "pb_fuse_frames_select", "pb_fuse_step_beam", "pb_forest_build", "pb_forest_free", "pb_score_forest",
+           "pb_fuse_step_forest", "pb_fuse_frames_forest", "pb_fuse_step_beam_forest", "pb_validate",
+           "pb_validate_states", "pb_strerror"]
 
 
 class PbError(RuntimeError):
@@ -46,7 +47,8 @@ class pb_host_view(C.Structure):
                 ("is_final", C.POINTER(C.c_uint8)), ("depth", C.POINTER(C.c_int32)),
                 ("parent", C.POINTER(C.c_int32)), ("arc_token", C.POINTER(C.c_int32)),
                 ("arc_score", C.POINTER(C.c_float)), ("acc", C.POINTER(C.c_double)),
-                ("root_score", C.POINTER(C.c_float)), ("root_next", C.POINTER(C.c_int32))]
+                ("root_score", C.POINTER(C.c_float)), ("root_next", C.POINTER(C.c_int32)),
+                ("p_root", C.POINTER(C.c_float)), ("eos_score", C.POINTER(C.c_float))]
 
 
 _lib = None
@@ -92,8 +94,6 @@ def load():
                                           C.c_int32, vp, vp, vp, vp]
     lib.pb_fuse_step_beam.restype = C.c_int
     lib.pb_fuse_step_beam.argtypes = [vp, vp, C.c_int64, vp, vp, C.c_float, C.c_int32, C.c_int32, vp, vp, vp, vp, vp]
-    lib.pb_diag_chase.restype = C.c_int
-    lib.pb_diag_chase.argtypes = [vp, C.c_int64, C.c_int32, C.c_int32, vp, vp]
     lib.pb_forest_build.restype = C.c_int
     lib.pb_forest_build.argtypes = [C.POINTER(vp), C.c_int32, C.POINTER(vp)]
     lib.pb_forest_free.restype = C.c_int
@@ -108,6 +108,10 @@ def load():
     lib.pb_fuse_step_beam_forest.restype = C.c_int
     lib.pb_fuse_step_beam_forest.argtypes = [vp, vp, C.c_int64, vp, vp, vp, C.c_float, C.c_int32, C.c_int32, vp, vp, vp,
                                              vp, vp]
+    lib.pb_validate.restype = C.c_int
+    lib.pb_validate.argtypes = [vp]
+    lib.pb_validate_states.restype = C.c_int
+    lib.pb_validate_states.argtypes = [vp, i32p, C.c_int64, i64p]
     lib.pb_strerror.restype = C.c_char_p
     lib.pb_strerror.argtypes = [C.c_int]
     _lib = lib
@@ -184,12 +188,30 @@ def pb_host_arrays(tree: Tree) -> dict:
     info = pb_info(tree)
     n, a, v = info["num_states"], info["num_arcs"], info["vocab_size"]
     sizes = dict(arc_begin=n, arc_count=n, fail=n, backoff=n, is_final=n, depth=n, parent=n, arc_token=a,
-                 arc_score=a, acc=n, root_score=v, root_next=v)
+                 arc_score=a, acc=n, root_score=v, root_next=v, p_root=n, eos_score=n)
     out = {}
     for name, cnt in sizes.items():
         ptr = getattr(view, name)
+        if not ptr:  # a NULL member (eos_score of a tree without the rule)
+            out[name] = None
+            continue
         out[name] = np.ctypeslib.as_array(ptr, shape=(cnt,)).copy() if cnt else np.zeros(0)
     return out
+
+
+def pb_validate(tree: Tree) -> int:
+    """Status code of the structural check (PB_OK / PB_ERANGE)."""
+    return int(load().pb_validate(tree.handle))
+
+
+def pb_validate_states(tree: Tree, states) -> int:
+    """Index of the first state id outside the tree, or -1 if all are valid (host array)."""
+    st = np.ascontiguousarray(states, dtype=np.int32)
+    bad = C.c_int64(-1)
+    rc = load().pb_validate_states(tree.handle, st.ctypes.data_as(C.POINTER(C.c_int32)), st.size, C.byref(bad))
+    if rc not in (PB_OK, PB_ERANGE):
+        raise PbError(rc, "pb_validate_states")
+    return int(bad.value) if rc == PB_ERANGE else -1
 
 
 def pb_state_prefix(tree: Tree, state: int) -> tuple:
@@ -238,10 +260,6 @@ def pb_fuse_step_beam(tree: Tree, d_logp, row_stride: int, d_hyp_scores, d_state
     _check(load().pb_fuse_step_beam(tree.handle, _dptr(d_logp), row_stride, _dptr(d_hyp_scores), _dptr(d_states_in),
                                     alpha, U, K, _dptr(d_tokens), _dptr(d_parents), _dptr(d_states_out),
                                     _dptr(d_scores_out), stream or None), "pb_fuse_step_beam")
-
-
-def pb_diag_chase(d_table, n: int, start: int, hops: int, d_out, stream: int = 0):
-    _check(load().pb_diag_chase(_dptr(d_table), n, start, hops, _dptr(d_out), stream or None), "pb_diag_chase")
 
 
 class Forest:

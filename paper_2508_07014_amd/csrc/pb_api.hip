@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <climits>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -26,9 +27,14 @@ int upload(pb_tree* tr, int device) {
   const size_t n_rn = h.root_next.size() * sizeof(int32_t);
   const size_t n_pr = h.p_root.size() * sizeof(float);
   const size_t n_rr = h.root_rec.size() * sizeof(pb::RootRec);
-  const size_t n_fs = h.final_score.size() * sizeof(float);
+  const size_t n_es = h.eos_score.size() * sizeof(float);
   const size_t total =
-      padded(n_state) + padded(n_arc) + padded(n_rs) + padded(n_rn) + padded(n_pr) + padded(n_rr) + padded(n_fs);
+      padded(n_state) + padded(n_arc) + padded(n_rs) + padded(n_rn) + padded(n_pr) + padded(n_rr) + padded(n_es);
+  // The wave kernels request the first arcs of a state without a condition, with the index clamped into the
+  // state's arc range; for a state without arcs (the last state of the table included) that reads the entry
+  // at arc_begin, i.e. up to one ArcRec past the arc table.  The sub-arrays that follow the arc table in the
+  // allocation make that read harmless; refuse a layout that would not.
+  if (total - (padded(n_state) + n_arc) < sizeof(pb::ArcRec)) return PB_EUNSUPPORTED;
   int prev = 0;
   if (hipGetDevice(&prev) != hipSuccess) { (void)hipGetLastError(); return PB_EHIP; }
   if (hipSetDevice(device) != hipSuccess) { (void)hipGetLastError(); return PB_EHIP; }
@@ -51,7 +57,7 @@ int upload(pb_tree* tr, int device) {
     tr->dev.root_next = static_cast<const int32_t*>(put(h.root_next.data(), n_rn));
     tr->dev.p_root = static_cast<const float*>(put(h.p_root.data(), n_pr));
     tr->dev.root_rec = static_cast<const pb::RootRec*>(put(h.root_rec.data(), n_rr));
-    tr->dev.final_score = n_fs ? static_cast<const float*>(put(h.final_score.data(), n_fs)) : nullptr;
+    tr->dev.eos_score = n_es ? static_cast<const float*>(put(h.eos_score.data(), n_es)) : nullptr;
     tr->dev.eos_id = h.eos_id;
     if (rc == PB_OK) rc = pb::prepare_wave_kernels();
     tr->dev.num_states = static_cast<int32_t>(h.state.size());
@@ -85,6 +91,10 @@ int pb_build(const int32_t* tokens, const int64_t* offsets, int64_t n_phrases, c
   pb_tree* tr = new (std::nothrow) pb_tree();
   if (!tr) return PB_ENOMEM;
   int rc = pb::compile_tree(tokens, offsets, n_phrases, weights, *opts, tr->host);
+  if (rc == PB_OK) {  // debug mode: bounds-check every index of the compiled arrays before anything uses them
+    const char* dbg = std::getenv("PB_DEBUG");
+    if (dbg && dbg[0] != '\0' && !(dbg[0] == '0' && dbg[1] == '\0')) rc = pb_validate(tr);
+  }
   if (rc == PB_OK && opts->device >= 0) rc = upload(tr, opts->device);
   if (rc != PB_OK) {
     delete tr;
@@ -138,6 +148,8 @@ int pb_host_arrays(const pb_tree* tree, pb_host_view* out) {
   out->acc = h.acc.data();
   out->root_score = h.root_score.data();
   out->root_next = h.root_next.data();
+  out->p_root = h.p_root.data();
+  out->eos_score = h.eos_score.empty() ? nullptr : h.eos_score.data();
   return PB_OK;
 }
 
@@ -196,7 +208,8 @@ int pb_fuse_frames_select(const pb_tree* tree, const float* d_logp, int64_t fram
   if (!d_logp || !d_states0 || !d_tokens || !d_states || !d_scores) return PB_EINVAL;
   if (row_stride < tree->dev.vocab_size || frame_stride < 0) return PB_EINVAL;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (pb::wave_path_ok(tree->dev, d_logp, frame_stride, row_stride))
+  // (the segment decoder keeps a flag in bit 30 of the state words it stores: larger trees take the plain kernel)
+  if (pb::wave_path_ok(tree->dev, d_logp, frame_stride, row_stride) && tree->dev.num_states < (1 << 30))
     return pb::launch_frames_wave(tree->dev, pb::TreePick{}, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, mode,
                                   d_tokens, d_states, d_scores, stream);
   return pb::launch_fuse(tree->dev, pb::TreePick{}, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, mode, d_tokens,
@@ -266,6 +279,8 @@ int pb_forest_build(const pb_tree* const* trees, int32_t n_trees, pb_forest** ou
     return rc;
   }
   f->proto = first->dev;
+  for (int32_t i = 0; i < n_trees; ++i)  // the largest member decides what the others may rely on (see pb_fuse_frames_forest)
+    if (trees[i]->dev.num_states > f->proto.num_states) f->proto.num_states = trees[i]->dev.num_states;
   f->count = n_trees;
   f->device = first->device;
   *out = f;
@@ -323,7 +338,7 @@ int pb_fuse_frames_forest(const pb_forest* forest, const float* d_logp, int64_t 
   if (row_stride < forest->proto.vocab_size || frame_stride < 0) return PB_EINVAL;
   const pb::TreePick pick{forest->d_table, d_tree_ids, forest->count};
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (pb::wave_path_ok(forest->proto, d_logp, frame_stride, row_stride))
+  if (pb::wave_path_ok(forest->proto, d_logp, frame_stride, row_stride) && forest->proto.num_states < (1 << 30))
     return pb::launch_frames_wave(forest->proto, pick, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B,
                                   mode, d_tokens, d_states, d_scores, stream);
   return pb::launch_fuse(forest->proto, pick, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, mode,
@@ -348,9 +363,63 @@ int pb_fuse_step_beam_forest(const pb_forest* forest, const float* d_logp, int64
                          d_parents, d_states_out, d_scores_out, static_cast<hipStream_t>(hip_stream));
 }
 
-int pb_diag_chase(const int32_t* d_table, int64_t n, int32_t start, int32_t hops, int32_t* d_out, void* hip_stream) {
-  if (!d_table || !d_out || n <= 0 || n > INT32_MAX || start < 0 || start >= n || hops < 0) return PB_EINVAL;
-  return pb::launch_chase(d_table, start, hops, d_out, static_cast<hipStream_t>(hip_stream));
+int pb_validate(const pb_tree* tree) {
+  if (!tree) return PB_EINVAL;
+  const pb::HostTree& h = tree->host;
+  const int64_t N = static_cast<int64_t>(h.state.size()), A = static_cast<int64_t>(h.arc.size());
+  const int32_t V = h.vocab_size;
+  auto in = [](int64_t x, int64_t lo, int64_t hi) { return x >= lo && x < hi; };
+  if (N < 1 || A != N - 1 || V <= 0) return PB_ERANGE;
+  if (static_cast<int64_t>(h.arc_begin.size()) != N || static_cast<int64_t>(h.arc_count.size()) != N ||
+      static_cast<int64_t>(h.fail.size()) != N || static_cast<int64_t>(h.depth.size()) != N ||
+      static_cast<int64_t>(h.parent.size()) != N || static_cast<int64_t>(h.backoff.size()) != N ||
+      static_cast<int64_t>(h.p_root.size()) != N || static_cast<int64_t>(h.arc_token.size()) != A ||
+      static_cast<int64_t>(h.arc_score.size()) != A || static_cast<int64_t>(h.root_score.size()) != V ||
+      static_cast<int64_t>(h.root_next.size()) != V || static_cast<int64_t>(h.root_rec.size()) != V)
+    return PB_ERANGE;
+  if (h.eos_id >= 0 && static_cast<int64_t>(h.eos_score.size()) != N) return PB_ERANGE;
+  int64_t next_arc = 0;
+  for (int64_t s = 0; s < N; ++s) {
+    // arc rows tile the arc table in state order; every arc stays inside it
+    if (h.arc_begin[s] != next_arc || h.arc_count[s] < 0 || next_arc + h.arc_count[s] > A) return PB_ERANGE;
+    next_arc += h.arc_count[s];
+    for (int64_t j = h.arc_begin[s]; j < h.arc_begin[s] + h.arc_count[s]; ++j) {
+      const int32_t tok = h.arc_token[j];
+      if (!in(tok, 0, V) || tok == h.blank_id || tok == h.eos_id) return PB_ERANGE;
+      if (j > h.arc_begin[s] && h.arc_token[j - 1] >= tok) return PB_ERANGE;  // strictly ascending rows
+      if (h.parent[j + 1] != s || h.depth[j + 1] != h.depth[s] + 1) return PB_ERANGE;  // arc j leads to state j + 1
+      if (h.arc[j].token != tok || h.arc[j].score != h.arc_score[j]) return PB_ERANGE;
+    }
+    // failure links lead to strictly shallower states, so every chain ends in the root
+    if (!in(h.fail[s], 0, N) || (s > 0 && h.depth[h.fail[s]] >= h.depth[s]) || (s == 0 && h.fail[s] != 0)) return PB_ERANGE;
+    const pb::StateRec& r = h.state[s];
+    if (r.arc_begin != h.arc_begin[s] || r.arc_count != h.arc_count[s] || r.fail != h.fail[s] ||
+        r.backoff != h.backoff[s])
+      return PB_ERANGE;
+  }
+  if (next_arc != A) return PB_ERANGE;
+  for (int32_t v = 0; v < V; ++v) {
+    const int32_t n = h.root_next[v];
+    if (!in(n, 0, N)) return PB_ERANGE;
+    if (n != 0 && (h.parent[n] != 0 || h.arc_token[n - 1] != v)) return PB_ERANGE;
+    const pb::RootRec& r = h.root_rec[v];
+    if (r.next != n || r.arc_begin != h.arc_begin[n] || r.arc_count != h.arc_count[n] || r.fail != h.fail[n] ||
+        r.backoff != h.backoff[n] || r.p_root != h.p_root[n])
+      return PB_ERANGE;
+  }
+  return PB_OK;
+}
+
+int pb_validate_states(const pb_tree* tree, const int32_t* states, int64_t n, int64_t* first_bad) {
+  if (!tree || n < 0 || (n > 0 && !states)) return PB_EINVAL;
+  const int64_t N = static_cast<int64_t>(tree->host.state.size());
+  for (int64_t i = 0; i < n; ++i) {
+    if (states[i] < 0 || states[i] >= N) {
+      if (first_bad) *first_bad = i;
+      return PB_ERANGE;
+    }
+  }
+  return PB_OK;
 }
 
 const char* pb_strerror(int code) {

@@ -191,12 +191,53 @@ int compile_tree(const int32_t* tokens, const int64_t* offsets, int64_t n_phrase
       t.root_score[t.arc_token[j]] = t.arc_score[j];
       t.root_next[t.arc_token[j]] = j + 1;
     }
+    if (o.eos_id >= 0) {
+      // EOS rule (Sec. II-C): the EOS boost of a state is the largest score any other token (the blank aside)
+      // gets in that state, plus the final weight of an end-of-phrase state.  It depends on the state alone,
+      // so it is tabulated here.  Per state: the arcs along the failure chain that no deeper chain state
+      // shadows, each with the backoffs paid before it (fp32, in the order a query adds them), and for the
+      // tokens no chain state overrides the total backoff plus the largest root score among them (fp32
+      // addition is monotone, so the maximum may be taken before the sum).
+      std::vector<int32_t> by_root_score;
+      by_root_score.reserve(V);
+      for (int32_t v = 0; v < V; ++v)
+        if (v != o.eos_id && v != o.blank_id) by_root_score.push_back(v);
+      std::stable_sort(by_root_score.begin(), by_root_score.end(),
+                       [&](int32_t a, int32_t b) { return t.root_score[a] > t.root_score[b]; });
+      std::vector<int32_t> seen(V, -1);
+      t.eos_score.assign(N, 0.0f);
+      for (int32_t s = 0; s < N; ++s) {
+        bool any = false;
+        float best = 0.0f;
+        float p = 0.0f;
+        for (int32_t x = s; x != 0; x = t.fail[x]) {
+          for (int32_t j = t.arc_begin[x]; j < t.arc_begin[x] + t.arc_count[x]; ++j) {
+            const int32_t v = t.arc_token[j];
+            if (seen[v] == s) continue;  // a deeper chain state has an arc on v
+            seen[v] = s;
+            const float c = p + t.arc_score[j];  // (phrases hold neither the EOS nor the blank)
+            if (!any || c > best) best = c;
+            any = true;
+          }
+          p = p + t.backoff[x];
+        }
+        for (const int32_t v : by_root_score) {
+          if (seen[v] == s) continue;
+          const float c = p + t.root_score[v];
+          if (!any || c > best) best = c;
+          any = true;
+          break;
+        }
+        t.eos_score[s] = (any ? best : 0.0f) + t.final_score[s];
+      }
+    }
     t.state.resize(N);
     for (int32_t s = 0; s < N; ++s) t.state[s] = {t.arc_begin[s], t.arc_count[s], t.fail[s], t.backoff[s]};
     t.root_rec.resize(V);
     for (int32_t v = 0; v < V; ++v) {
       const int32_t n = t.root_next[v];
-      t.root_rec[v] = {n, t.arc_begin[n], t.arc_count[n], t.fail[n], t.backoff[n], t.p_root[n], 0, 0};
+      t.root_rec[v] = {n, t.arc_begin[n], t.arc_count[n], t.fail[n], t.backoff[n], t.p_root[n],
+                       t.eos_score.empty() ? 0.0f : t.eos_score[n], 0};
     }
     t.arc.resize(t.arc_token.size());
     for (size_t j = 0; j < t.arc.size(); ++j) t.arc[j] = {t.arc_token[j], t.arc_score[j]};

@@ -43,221 +43,13 @@
 #include <type_traits>
 
 #include "pb_kernels.hpp"
+#include "pb_wave.hpp"
 
 namespace pb {
 
 namespace {
 
-#define PB_AS4 __attribute__((address_space(4)))
-
-constexpr int kChunk = 1024;  // tokens per chunk: 16 per lane
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v8i __attribute__((ext_vector_type(8)));
-using u64 = unsigned long long;
-
-// Scalar-load views: the tree is never written while kernels run, so wave-uniform reads may go
-// through the constant address space (scalar cache).
-struct TreeView {
-  const v4i PB_AS4* state;     // StateRec as four dwords: arc_begin, arc_count, fail, backoff bits
-  const float PB_AS4* p_root;
-  const int32_t PB_AS4* root_next;
-  const v8i PB_AS4* root_rec;  // RootRec as eight dwords
-  const ArcRec* arc;
-  const float* root_score;
-  int num_states, V, blank;
-};
-
-__device__ __forceinline__ TreeView make_view(const DeviceTree& t) {
-  TreeView v;
-  v.state = (const v4i PB_AS4*)t.state;
-  v.p_root = (const float PB_AS4*)t.p_root;
-  v.root_next = (const int32_t PB_AS4*)t.root_next;
-  v.root_rec = (const v8i PB_AS4*)t.root_rec;
-  v.arc = t.arc;
-  v.root_score = t.root_score;
-  v.num_states = t.num_states;
-  v.V = t.vocab_size;
-  v.blank = t.blank_id;
-  return v;
-}
-
-// Values that are wave-uniform by construction, told to the compiler (keeps them in SGPRs and the
-// loads they address on the scalar path).
-__device__ __forceinline__ int uniform_i(int v) { return __builtin_amdgcn_readfirstlane(v); }
-__device__ __forceinline__ float uniform_f(float v) {
-  return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v)));
-}
-
-// Order-preserving fp32 <-> uint32 (every real value, -inf included, maps above 0).
-__device__ __forceinline__ unsigned ukey(float f) {
-  const int b = __float_as_int(f);
-  return static_cast<unsigned>(b) ^ (static_cast<unsigned>(b >> 31) | 0x80000000u);
-}
-__device__ __forceinline__ float ukey_val(unsigned k) {
-  const unsigned m = (k & 0x80000000u) ? 0x80000000u : 0xffffffffu;
-  return __uint_as_float(k ^ m);
-}
-
-template <int CTRL>
-__device__ __forceinline__ unsigned dpp0(unsigned v) {  // lanes without a source read 0
-  return static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xf, 0xf, true));
-}
-// Wave-wide unsigned max; 0 is the identity.  The result is wave-uniform (read from lane 63).
-__device__ __forceinline__ unsigned wave_max_u(unsigned v) {
-  v = max(v, dpp0<0x111>(v));  // row_shr:1
-  v = max(v, dpp0<0x112>(v));  // row_shr:2
-  v = max(v, dpp0<0x114>(v));  // row_shr:4
-  v = max(v, dpp0<0x118>(v));  // row_shr:8
-  v = max(v, dpp0<0x142>(v));  // row_bcast:15
-  v = max(v, dpp0<0x143>(v));  // row_bcast:31
-  return static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(v), 63));
-}
-// Wave-wide min of non-negative ints (INT_MAX = nothing).
-__device__ __forceinline__ int wave_min_nn(int v) {
-  return INT_MAX - static_cast<int>(wave_max_u(static_cast<unsigned>(INT_MAX - v)));
-}
-// The lane id again, but opaque to the optimiser: values derived from it inside a rarely taken branch
-// are then computed there instead of being hoisted out of the frame loop into long-lived registers.
-__device__ __forceinline__ int opaque(int v) {
-  asm volatile("" : "+v"(v));
-  return v;
-}
-__device__ __forceinline__ int first_lane(u64 mask) { return __builtin_ctzll(mask); }
-
-__device__ __forceinline__ int tok_of(int j, int lane) { return 256 * (j >> 2) + 4 * lane + (j & 3); }
-// Does the lane's slot j hold chunk-relative token `rel` (wave-uniform)?  Written so that the slot
-// test stays on the scalar side and no per-slot token ids have to live in vector registers.
-__device__ __forceinline__ bool slot_is(int j, int lane, int rel) {
-  const int slot = ((rel >> 8) << 2) | (rel & 3);  // uniform
-  return (slot == j) && (lane == ((rel >> 2) & 63)) && (static_cast<unsigned>(rel) < static_cast<unsigned>(kChunk));
-}
-
-__device__ __forceinline__ bool valid_state(const TreeView& t, int s) {
-  return static_cast<unsigned>(s) < static_cast<unsigned>(t.num_states);
-}
-
-struct Rec {  // wave-uniform copy of a StateRec
-  int begin, count, fail;
-  float backoff;
-};
-__device__ __forceinline__ Rec load_rec(const TreeView& t, int s) {
-  const v4i r = t.state[s];
-  Rec o;
-  o.begin = r.x;
-  o.count = r.y;
-  o.fail = r.z;
-  o.backoff = __int_as_float(r.w);
-  return o;
-}
-
-struct Cursor {  // wave-uniform decoding state of one hypothesis
-  int s;
-  Rec rec;
-  float p_root;
-};
-__device__ __forceinline__ Cursor cursor_at(const TreeView& t, int s) {
-  Cursor c;
-  c.s = s;
-  c.rec = load_rec(t, s);
-  c.p_root = t.p_root[s];
-  return c;
-}
-__device__ __forceinline__ Cursor cursor_from_root_rec(const v8i& r) {
-  Cursor c;
-  c.s = r.s0;
-  c.rec.begin = r.s1;
-  c.rec.count = r.s2;
-  c.rec.fail = r.s3;
-  c.rec.backoff = __int_as_float(r.s4);
-  c.p_root = __int_as_float(r.s5);
-  return c;
-}
-
-// Selection rule (enum pb_select_mode): 0 = single-stage fused arg-max, 1 = two-stage, 2 = two-stage
-// with the CTC repeat rule (Sec. II-C).  In the two-stage modes the blank is never a candidate of
-// the boosted re-selection: its column carries NaN, which neither fmaxf nor an equality test ever
-// selects, so an excluded token costs nothing in the reductions.
-//
-// alpha * (p_root + root_score[v]) for the lane's 16 tokens; the blank column boosts by 0 (SEL == 0)
-// or is excluded (SEL != 0).
-template <int SEL>
-__device__ __forceinline__ void make_base_boost(int cb, int lane, int blank, float p_root, float alpha,
-                                                const float (&rw)[16], float (&c)[16]) {
-#pragma unroll
-  for (int j = 0; j < 16; ++j) {
-    const float boost = slot_is(j, lane, blank - cb) ? (SEL == 0 ? 0.0f : NAN) : __fadd_rn(p_root, rw[j]);
-    c[j] = __fmul_rn(alpha, boost);
-  }
-}
-
-// Loads the lane's 16 values of chunk `cb` of a V-long fp32 array; positions >= V read as `fill`.
-template <bool FULL>
-__device__ __forceinline__ void load16(const float* __restrict__ base, int cb, int V, int lane, float fill,
-                                       float (&x)[16]) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int v = cb + 256 * i + 4 * lane;
-    if (FULL || v < V) {  // V % 4 == 0: a 16-byte group is entirely inside or outside the row
-      const float4 q = *reinterpret_cast<const float4*>(base + v);
-      x[4 * i + 0] = q.x; x[4 * i + 1] = q.y; x[4 * i + 2] = q.z; x[4 * i + 3] = q.w;
-    } else {
-      x[4 * i + 0] = x[4 * i + 1] = x[4 * i + 2] = x[4 * i + 3] = fill;
-    }
-  }
-}
-
-__device__ __forceinline__ void store_row_lds(float* row, int lane, const float (&x)[16]) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-    *reinterpret_cast<float4*>(row + 256 * i + 4 * lane) = make_float4(x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]);
-}
-
-// Lowest token (chunk-relative) whose fused value equals M; g are the lane's four group maxima.
-__device__ __forceinline__ int first_token_equal(const float (&f)[16], const float (&g)[4], float M, int lane) {
-  const u64 b0 = __ballot(g[0] == M), b1 = __ballot(g[1] == M), b2 = __ballot(g[2] == M), b3 = __ballot(g[3] == M);
-  int gi;
-  u64 bm, e0, e1, e2;  // the fourth token of a group needs no ballot: it is the one left
-  if (b0) {
-    gi = 0; bm = b0;
-    e0 = __ballot(f[0] == M); e1 = __ballot(f[1] == M); e2 = __ballot(f[2] == M);
-  } else if (b1) {
-    gi = 1; bm = b1;
-    e0 = __ballot(f[4] == M); e1 = __ballot(f[5] == M); e2 = __ballot(f[6] == M);
-  } else if (b2) {
-    gi = 2; bm = b2;
-    e0 = __ballot(f[8] == M); e1 = __ballot(f[9] == M); e2 = __ballot(f[10] == M);
-  } else if (b3) {
-    gi = 3; bm = b3;
-    e0 = __ballot(f[12] == M); e1 = __ballot(f[13] == M); e2 = __ballot(f[14] == M);
-  } else {
-    return 0;  // only with NaN inputs (precondition violation): stay in range
-  }
-  const int L = first_lane(bm);
-  const u64 bit = 1ull << L;
-  const int k = (e0 & bit) ? 0 : (e1 & bit) ? 1 : (e2 & bit) ? 2 : 3;
-  return 256 * gi + 4 * L + k;
-}
-
-// Per-wave token marks: one bit per token of the current chunk (32 dwords of LDS).  LDS operations
-// of one wave execute in order, so clear -> set -> test needs no barrier inside the wave.
-constexpr int kTagWords = kChunk / 32;
-__device__ __forceinline__ void tags_clear(unsigned* bits, int lane) {
-  if (lane < kTagWords) bits[lane] = 0u;
-}
-__device__ __forceinline__ void tag_set(unsigned* bits, int tk) { atomicOr(&bits[tk >> 5], 1u << (tk & 31)); }
-__device__ __forceinline__ bool tag_test(const unsigned* bits, int tk) { return ((bits[tk >> 5] >> (tk & 31)) & 1u) != 0u; }
-
-__device__ __forceinline__ float max4(float a, float b, float c, float d) { return fmaxf(fmaxf(a, b), fmaxf(c, d)); }
-
-// Stage 1 of the two-stage rule on one chunk: the unboosted row maximum and its lowest token.
-__device__ __forceinline__ void plain_argmax(const float (&x)[16], int lane, float& M0, int& v0) {
-  float g[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) g[i] = max4(x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]);
-  M0 = ukey_val(wave_max_u(ukey(max4(g[0], g[1], g[2], g[3]))));
-  v0 = first_token_equal(x, g, M0, lane);
-}
+using namespace wv;
 
 // ------------------------------------------------------------------------------------------------
 // Base boosts of a row with V <= 1024 for the lane's 16 tokens; the root scores come from memory
@@ -319,6 +111,12 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
   float f[16];
 #pragma unroll
   for (int j = 0; j < 16; ++j) f[j] = __fadd_rn(x[j], c[j]);
+  if (t.eos >= 0) {  // EOS rule (Sec. II-C): the EOS token is boosted by the value tabulated for the state
+    const float ce = __fmul_rn(alpha, cur.eos_boost);
+    const int ln = opaque(lane);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) f[j] = slot_is(j, ln, t.eos) ? __fadd_rn(x[j], ce) : f[j];
+  }
   if (chain) store_row_lds(row, lane, x);
   row_in_lds = chain;
   const Cursor start = cur;
@@ -467,7 +265,7 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
     } else {
       out_val = base_val;
       out_tok = base_tok;
-      if (base_tok != t.blank) {  // the blank keeps the state
+      if (base_tok != t.blank && base_tok != t.eos) {  // the blank and the EOS keep the state
         if (base_tok == vb) {
           cur = cursor_from_root_rec(rr);
         } else {
@@ -487,55 +285,57 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
   cur.rec.fail = uniform_i(cur.rec.fail);
   cur.rec.backoff = uniform_f(cur.rec.backoff);
   cur.p_root = uniform_f(cur.p_root);
+  cur.eos_boost = uniform_f(cur.eos_boost);
   out_val = uniform_f(out_val);
 }
 
-// Segment boundaries of the multi-frame decoder.  A segment that does not begin the
-// call starts from a guess instead of the root: the state the frame before it leads to when its base
-// winner under root-state boosts is taken -- which is what the true decode does in most frames.  The
-// segment that ends there computes the same guess from the same row, compares it with its actual end
-// state (under the CTC rule also with its last label) and, if they agree, sets kGuessOk in the state
-// word it stores for its last frame; the fix-up pass
-// then has nothing to re-run for the next segment, and clears the bit.  States stay below 2^30 for this.
-constexpr int kGuessOk = 1 << 30;
-
-// c0: the base boosts of the root state for the rule (make_base_boost<SEL> with p_root = 0).  Under the
-// two-stage rules a frame whose raw arg-max is the blank keeps a state nobody knows here: the guess is
-// then the root, and mostly wrong.
+// Boundary guess of the multi-frame decoder for rows of up to 1024 tokens: the state (and label) assumed after
+// frame f, from the rows alone.  Going back from frame f, a frame whose winner under root-state boosts keeps the
+// state (the blank; under the two-stage rules a blank raw arg-max) is skipped; the first frame that moves the
+// state gives root_next[its winner] -- what the true decode does in most frames.  Reaching the first frame of
+// the call gives the call's start state, kLookBack skipped frames give the root.  The label is the winner of
+// frame f itself.  Both neighbours of a boundary call this with the same rows and get the same answer.
+//   x: row of frame f (registers, overwritten), rp: its address, c0: root-state base boosts of the rule.
 template <bool FULL, int SEL>
-__device__ __forceinline__ void guess_state(const TreeView& t, const float (&x)[16], const float (&c0)[16], int lane,
-                                            int& state, int& label) {
-  if constexpr (SEL != 0) {
-    float M0;
-    int v0;
-    plain_argmax(x, lane, M0, v0);
-    if (v0 == t.blank) {
-      state = 0;
-      label = uniform_i(v0);
+__device__ __forceinline__ void guess_boundary_1k(const TreeView& t, float (&x)[16], const float* rp,
+                                                  int64_t frame_stride, int f, const int32_t* __restrict__ states0,
+                                                  int b, const float (&c0)[16], int lane, int& state, int& label) {
+  label = -1;
+  for (int k = 0;; ++k) {
+    bool keep = false;
+    int w = 0;
+    if constexpr (SEL != 0) {
+      float M0;
+      plain_argmax(x, lane, M0, w);
+      w = uniform_i(w);
+      keep = w == t.blank;
+    }
+    if (!keep) {
+      float fz[16], g[4];
+#pragma unroll
+      for (int j = 0; j < 16; ++j) fz[j] = __fadd_rn(x[j], c0[j]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) g[i] = max4(fz[4 * i], fz[4 * i + 1], fz[4 * i + 2], fz[4 * i + 3]);
+      const float M = ukey_val(wave_max_u(ukey(max4(g[0], g[1], g[2], g[3]))));
+      w = uniform_i(first_token_equal(fz, g, M, lane));
+      keep = w == t.blank || w == t.eos;
+    }
+    if (k == 0) label = w;
+    if (!keep) {
+      state = uniform_i(t.root_next[w]);
       return;
     }
-  }
-  float f[16], g[4];
-#pragma unroll
-  for (int j = 0; j < 16; ++j) f[j] = __fadd_rn(x[j], c0[j]);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) g[i] = max4(f[4 * i], f[4 * i + 1], f[4 * i + 2], f[4 * i + 3]);
-  const float M = ukey_val(wave_max_u(ukey(max4(g[0], g[1], g[2], g[3]))));
-  const int v = uniform_i(first_token_equal(f, g, M, lane));
-  label = v;
-  state = v == t.blank ? 0 : uniform_i(t.root_next[v]);  // (single-stage rule: a blank keeps an unknown state)
-}
-
-// State word of a stored frame without the boundary bit (an invalid frame holds -1 and stays as it is).
-__device__ __forceinline__ int plain_state(int word) { return word < 0 ? word : (word & ~kGuessOk); }
-
-__device__ __forceinline__ void fill_invalid(int B, int b, int f0, int f1, int32_t* tokens, int32_t* states,
-                                             float* scores, int lane) {
-  for (int f = f0 + lane; f < f1; f += 64) {
-    const size_t o = static_cast<size_t>(f) * B + b;
-    tokens[o] = -1;
-    states[o] = -1;
-    scores[o] = NAN;
+    if (f - k == 0) {  // nothing since the start of the call has moved the state
+      const int s0 = uniform_i(states0[b]);
+      state = valid_state(t, s0) ? s0 : 0;
+      return;
+    }
+    if (k + 1 >= kLookBack) {
+      state = 0;
+      return;
+    }
+    rp -= frame_stride;
+    load16<FULL>(rp, 0, t.V, lane, -INFINITY, x);
   }
 }
 
@@ -545,28 +345,29 @@ __device__ __forceinline__ void fill_invalid(int B, int b, int f0, int f1, int32
 // first frame whose outcome equals the one already stored -- the out-state in `states` and, under
 // the CTC rule where the label feeds the next frame, the token in `tokens` (the stored trajectory is
 // then valid from there on).
-//   Rows travel through a ring of register buffers: the frame in hand and the one or two after it.
-//   EDGE (pass 1 of the multi-frame decoder, single-stage rule): the range starts from a guess when it
-//   does not begin the call (f0 > 0) and marks its last state word when its own guess for the next
-//   range (f1 < T) turns out right.
+//   Rows travel through a ring of three register buffers: the frame in hand and the two after it.
+//   EDGE (pass 1 of the multi-frame decoder): the range starts from a guess when it does not begin the call
+//   (f0 > 0) and marks its last state word when its own guess for the next range (f1 < T) turns out right.
 template <bool COMPARE, bool FULL, int SEL, bool EDGE>
 __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
                                               int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s_in,
-                                              int last_in, int T, int32_t* __restrict__ tokens,
-                                              int32_t* __restrict__ states, float* __restrict__ scores, float* row,
-                                              unsigned* tags, int lane) {
+                                              int last_in, int T, const int32_t* __restrict__ states0,
+                                              int32_t* __restrict__ tokens, int32_t* __restrict__ states,
+                                              float* __restrict__ scores, float* row, unsigned* tags, int lane) {
   if (f0 >= f1) return;
   constexpr bool GUESS = EDGE && !COMPARE;
   const int V = t.V;
   const float* rp = logp + static_cast<size_t>(b) * row_stride + static_cast<size_t>(f0) * frame_stride;
-  constexpr int NB = COMPARE ? 2 : 3;  // ring size: a re-run is short, one row ahead is enough there
+  constexpr int NB = 3;  // ring size
   // Batches of 64 arcs requested at the start of a frame: 256 arcs cover all but a few states; the two-stage
   // rules hold more state in registers and take half of that, a re-run (16 waves per workgroup) one batch.
   constexpr int kEarlyBatches = COMPARE ? 1 : (SEL == 0 ? 4 : 2);
   float xb[NB][16], c[16];
   load16<FULL>(rp, 0, V, lane, -INFINITY, xb[0]);
-  if (NB == 3 && f0 + 1 < f1) load16<FULL>(rp + frame_stride, 0, V, lane, -INFINITY, xb[1]);
+  if (f0 + 1 < f1) load16<FULL>(rp + frame_stride, 0, V, lane, -INFINITY, xb[1]);
   load16<FULL>(t.root_score, 0, V, lane, 0.0f, c);  // needs no state: requested before the state is looked at
+  StoredLane<SEL == 2> stored;
+  if (COMPARE) stored.fetch(lane, f0, f1, B, b, tokens, states);
   int s = uniform_i(s_in);
   int last = -1;
   if (SEL == 2) last = uniform_i(last_in);
@@ -576,7 +377,7 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
     load16<FULL>(rp - frame_stride, 0, V, lane, -INFINITY, xw);
     make_base_boost<SEL>(0, lane, t.blank, 0.0f, alpha, c, c0);
     int label;
-    guess_state<FULL, SEL>(t, xw, c0, lane, s, label);
+    guess_boundary_1k<FULL, SEL>(t, xw, rp - frame_stride, frame_stride, f0 - 1, states0, b, c0, lane, s, label);
     if (SEL == 2) last = label;
   }
   if (!valid_state(t, s)) {
@@ -586,22 +387,11 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
   Cursor cur = cursor_at(t, s);
   float c_p = cur.p_root;
   make_base_boost<SEL>(0, lane, t.blank, c_p, alpha, c, c);  // element-wise, in place
-  // Outputs.  The single-stage decode keeps those of up to 64 consecutive frames in the lanes (frame
-  // base + l in lane l) and writes them together, so that no store sits in the in-order queue of the
-  // loads; a re-run writes frame by frame, right after it has compared with what is stored, and so do
-  // the two-stage rules, whose extra state would otherwise push registers to scratch memory.
-  constexpr bool DEFER = !COMPARE && SEL == 0;
-  int base = f0;
-  int o_tok = 0, o_st = 0;
-  float o_sc = 0.0f;
-  auto flush = [&](int count) {
-    if (lane < count) {
-      const size_t o = static_cast<size_t>(base + lane) * B + b;
-      tokens[o] = o_tok;
-      states[o] = o_st;
-      scores[o] = o_sc;
-    }
-  };
+  // Outputs.  The single-stage decode and every re-run keep those of up to 64 consecutive frames in the lanes
+  // and write them together, so that no store sits in the in-order queue of the loads; pass 1 of the two-stage
+  // rules, whose extra state would otherwise push registers to scratch memory, writes frame by frame.
+  constexpr bool DEFER = COMPARE || SEL == 0;
+  LaneOut out{f0, 0, 0, 0.0f};
   size_t o = static_cast<size_t>(f0) * B + b;
   bool row_in_lds = false;  // the LDS row holds the raw row of the frame decoded last
   // One frame with its row in ring slot U.  STEADY frames request the row NB-1 frames ahead without a
@@ -623,28 +413,26 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
                         val, tok, row_in_lds);
     const int word = cur.s;
     if (!DEFER) {
-      int stored = -1, stored_tok = tok;
-      if (COMPARE) {
-        stored = plain_state(uniform_i(__hip_atomic_load(states + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)));
-        if (SEL == 2) stored_tok = uniform_i(__hip_atomic_load(tokens + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-      }
       if (lane == 0) {
         tokens[o] = tok;
         states[o] = word;
         scores[o] = val;
       }
-      if (COMPARE && stored == cur.s && stored_tok == tok) return true;
       o += B;
     } else {
-      const int slot = f - base;
-      if (lane == slot) {
-        o_tok = tok;
-        o_st = word;
-        o_sc = val;
+      const int slot = f - out.base;
+      out.put(lane, f, tok, word, val);
+      if (COMPARE) {
+        // met the stored trajectory: this frame is written too (its score may differ), the rest stands
+        if (stored.state_at(slot) == word && (SEL != 2 || stored.token_at(slot) == tok)) {
+          out.template flush<true>(lane, slot + 1, B, b, tokens, states, scores);
+          return true;
+        }
       }
-      if (slot == 63) {
-        flush(64);
-        base = f + 1;
+      if (slot == 63 && f + 1 < f1) {  // (the last group is written at the end, after the boundary bit is known)
+        out.template flush<COMPARE>(lane, 64, B, b, tokens, states, scores);
+        out.base = f + 1;
+        if (COMPARE) stored.fetch(lane, f + 1, f1, B, b, tokens, states);
       }
     }
     if (SEL == 2) last = tok;
@@ -656,16 +444,12 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
   for (; fb + NB <= f1; fb += NB) {  // whole turns of the ring: straight-line code
     if (do_frame(integral_constant<int, 0>{}, integral_constant<bool, true>{}, fb)) return;
     if (do_frame(integral_constant<int, 1>{}, integral_constant<bool, true>{}, fb + 1)) return;
-    if constexpr (NB == 3) {
-      if (do_frame(integral_constant<int, 2>{}, integral_constant<bool, true>{}, fb + 2)) return;
-    }
+    if (do_frame(integral_constant<int, 2>{}, integral_constant<bool, true>{}, fb + 2)) return;
   }
   if (fb < f1 && do_frame(integral_constant<int, 0>{}, integral_constant<bool, false>{}, fb)) return;
-  if constexpr (NB == 3) {
-    if (fb + 1 < f1 && do_frame(integral_constant<int, 1>{}, integral_constant<bool, false>{}, fb + 1)) return;
-  }
+  if (fb + 1 < f1 && do_frame(integral_constant<int, 1>{}, integral_constant<bool, false>{}, fb + 1)) return;
   if (guessable && f1 < T) {
-    // The guess the next range starts from, made here from the same row; if it is what this range really
+    // The guess the next range starts from, made here from the same rows; if it is what this range really
     // ends in, the last state word says so.
     float xl[16], c0[16];
     if (row_in_lds) {  // the usual case: the last frame left its raw row in LDS
@@ -679,230 +463,25 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
     }
     rebuild_base_boost<FULL, SEL>(t, opaque(lane), 0.0f, alpha, c0);
     int g, glabel;
-    guess_state<FULL, SEL>(t, xl, c0, lane, g, glabel);
+    guess_boundary_1k<FULL, SEL>(t, xl, rp - frame_stride, frame_stride, f1 - 1, states0, b, c0, lane, g, glabel);
     if (g == cur.s && (SEL != 2 || glabel == last)) {
       if (DEFER) {
-        if (lane == f1 - 1 - base) o_st |= kGuessOk;
+        if (lane == f1 - 1 - out.base) out.st |= kGuessOk;
       } else if (lane == 0) {
         states[static_cast<size_t>(f1 - 1) * B + b] = cur.s | kGuessOk;
       }
     }
   }
-  if (DEFER) flush(f1 - base);
+  if (DEFER) out.template flush<COMPARE>(lane, f1 - out.base, B, b, tokens, states, scores);
 }
 
-// ------------------------------------------------------------------------------------------------
-// Rows longer than 1024 tokens: the same scheme chunk by chunk (tags used for every arc).
-struct Win {  // wave-uniform result of one chunk or frame
-  float val;
-  int tok;
-  int next;
-};
-
-// `excl` (SEL == 2): a token barred from the selection, or -1.
-template <int SEL>
-__device__ __forceinline__ Win decide_chunk(const TreeView& t, int s, int cb, const float (&x)[16], const float (&c)[16],
-                                            float alpha, float* row, unsigned* tags, int lane, int excl) {
-  float f[16], g[4];
-#pragma unroll
-  for (int j = 0; j < 16; ++j) f[j] = __fadd_rn(x[j], c[j]);
-  if (SEL == 2 && excl >= 0) {
-#pragma unroll
-    for (int j = 0; j < 16; ++j) f[j] = slot_is(j, lane, excl - cb) ? NAN : f[j];
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i) g[i] = max4(f[4 * i], f[4 * i + 1], f[4 * i + 2], f[4 * i + 3]);
-  const float M = ukey_val(wave_max_u(ukey(max4(g[0], g[1], g[2], g[3]))));
-  const int vb = first_token_equal(f, g, M, lane);
-
-  bool have_arcs = false;
-  float bf = -INFINITY;
-  int btok = INT_MAX, bchild = 0;
-  if (s != 0) {
-    store_row_lds(row, lane, x);
-    tags_clear(tags, lane);
-    float p = 0.0f;
-    int xs = s, level = 0;
-    while (xs != 0) {
-      const Rec r = load_rec(t, xs);
-      for (int j0 = 0; j0 < r.count; j0 += 64) {
-        const int j = j0 + lane;
-        if (j < r.count) {
-          const ArcRec a = t.arc[r.begin + j];
-          const unsigned rel = static_cast<unsigned>(a.token - cb);
-          if (rel < static_cast<unsigned>(kChunk)) {
-            bool shadowed = (SEL == 2 && a.token == excl);
-            if (level > 0) shadowed = shadowed || tag_test(tags, rel);  // a deeper chain state owns this token
-            tag_set(tags, rel);
-            if (!shadowed) {
-              const float fa = __fadd_rn(row[rel], __fmul_rn(alpha, __fadd_rn(p, a.score)));
-              if (fa > bf || (fa == bf && static_cast<int>(rel) < btok)) {
-                bf = fa;
-                btok = static_cast<int>(rel);
-                bchild = r.begin + j + 1;
-              }
-            }
-          }
-        }
-      }
-      have_arcs = have_arcs || r.count > 0;
-      p = __fadd_rn(p, r.backoff);
-      xs = uniform_i(r.fail);
-      ++level;
-    }
-  }
-
-  Win w;
-  bool arc_wins = false;
-  int va = INT_MAX, achild = 0;
-  float MA = 0.0f, base_val = M;
-  int base_tok = vb;
-  const bool mine0 = btok != INT_MAX;
-  if (have_arcs && __ballot(mine0) != 0) {  // some arc fell into this chunk
-    MA = ukey_val(wave_max_u(mine0 ? ukey(bf) : 0u));
-    const bool mine = mine0 && bf == MA;
-    va = wave_min_nn(mine ? btok : INT_MAX);
-    achild = __builtin_amdgcn_readlane(bchild, first_lane(__ballot(mine && btok == va)));
-    const bool vb_overridden = uniform_i(static_cast<int>(tag_test(tags, vb))) != 0;
-    if (MA > M) {
-      arc_wins = true;
-    } else if (!vb_overridden) {
-      arc_wins = (MA == M) && (va < vb);
-    } else {
-      unsigned k[16], mk = 0u;
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const bool out = tag_test(tags, tok_of(j, lane)) || (SEL != 0 && f[j] != f[j]);
-        k[j] = out ? 0u : ukey(f[j]);
-        mk = max(mk, k[j]);
-      }
-      const unsigned Mk = wave_max_u(mk);
-      bool have_base = Mk != 0u;
-      if (have_base) {
-        base_val = ukey_val(Mk);
-        int l2 = INT_MAX;
-#pragma unroll
-        for (int j = 15; j >= 0; --j) l2 = (k[j] != 0u && f[j] == base_val) ? tok_of(j, lane) : l2;
-        base_tok = wave_min_nn(l2);
-        have_base = base_tok != INT_MAX;
-      }
-      arc_wins = !have_base || MA > base_val || (MA == base_val && va < base_tok);
-    }
-  }
-  if (arc_wins) {
-    w.val = MA;
-    w.tok = cb + va;
-    w.next = achild;
-  } else {
-    w.val = base_val;
-    w.tok = cb + base_tok;
-    w.next = (w.tok == t.blank) ? s : t.root_next[w.tok];
-  }
-  return w;
-}
-
-template <bool COMPARE, int SEL>
-__device__ __forceinline__ void run_frames_multi(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
-                                                 int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s_in,
-                                                 int last_in, int32_t* __restrict__ tokens, int32_t* __restrict__ states,
-                                                 float* __restrict__ scores, float* row, unsigned* tags, int lane) {
-  int s = uniform_i(s_in);
-  int last = -1;
-  if (SEL == 2) last = uniform_i(last_in);
-  if (!valid_state(t, s)) {
-    fill_invalid(B, b, f0, f1, tokens, states, scores, lane);
-    return;
-  }
-  const int V = t.V;
-  const int nch = (V + kChunk - 1) / kChunk;
-  const float* rp = logp + static_cast<size_t>(b) * row_stride + static_cast<size_t>(f0) * frame_stride;
-  size_t o = static_cast<size_t>(f0) * B + b;
-  float x[2][16], rw[16], c[16];
-  for (int f = f0; f < f1; ++f) {
-    Win best{0.0f, -1, s};
-    bool decided = false;
-    if constexpr (SEL != 0) {
-      // stage 1: unboosted arg-max over the whole row; the chunks are read again (from cache) below
-      for (int ch = 0; ch < nch; ++ch) {
-        load16<false>(rp, ch * kChunk, V, lane, -INFINITY, x[0]);
-        float M0;
-        int v0;
-        plain_argmax(x[0], lane, M0, v0);
-        if (best.tok < 0 || M0 > best.val) {  // chunks ascend, so ties keep the lower token
-          best.val = uniform_f(M0);
-          best.tok = uniform_i(ch * kChunk + v0);
-        }
-      }
-      decided = best.tok == t.blank || (SEL == 2 && best.tok == last);
-    }
-    if (!decided) {
-      const float p_root = uniform_f(t.p_root[s]);
-      for (int excl = -1;;) {
-        best = Win{0.0f, -1, s};
-        load16<false>(rp, 0, V, lane, -INFINITY, x[0]);
-        for (int ch0 = 0; ch0 < nch; ch0 += 2) {
-#pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            const int ch = ch0 + u;
-            if (ch < nch) {
-              if (ch + 1 < nch) load16<false>(rp, (ch + 1) * kChunk, V, lane, -INFINITY, x[(u + 1) % 2]);
-              load16<false>(t.root_score, ch * kChunk, V, lane, 0.0f, rw);
-              make_base_boost<SEL>(ch * kChunk, lane, t.blank, p_root, alpha, rw, c);
-              const Win w = decide_chunk<SEL>(t, s, ch * kChunk, x[u], c, alpha, row, tags, lane, excl);
-              if (best.tok < 0 || w.val > best.val) best = w;  // chunks ascend, so ties keep the lower token
-              best.val = uniform_f(best.val);
-              best.tok = uniform_i(best.tok);
-              best.next = uniform_i(best.next);
-            }
-          }
-        }
-        if (SEL != 2 || excl >= 0 || best.tok != last) break;
-        excl = last;  // the previous label won the re-selection: decide again without it
-      }
-    }
-    int stored = 0, stored_tok = 0;
-    if (COMPARE) {
-      stored = uniform_i(__hip_atomic_load(states + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-      if (SEL == 2) stored_tok = uniform_i(__hip_atomic_load(tokens + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    }
-    if (lane == 0) {
-      tokens[o] = best.tok;
-      states[o] = best.next;
-      scores[o] = best.val;
-    }
-    s = best.next;
-    if (COMPARE && stored == s && (SEL != 2 || stored_tok == best.tok)) return;
-    if (SEL == 2) last = best.tok;
-    rp += frame_stride;
-    o += B;
-  }
-}
-
-// MODE 0: V == 1024, 1: V < 1024, 2: V > 1024 (multi-chunk).
-template <bool COMPARE, int MODE, int SEL, bool EDGE = false>
-__device__ __forceinline__ void run_frames(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
-                                           int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s, int last,
-                                           int T, int32_t* __restrict__ tokens, int32_t* __restrict__ states,
-                                           float* __restrict__ scores, float* row, unsigned* tags, int lane) {
-  if constexpr (MODE == 0)
-    run_frames_1k<COMPARE, true, SEL, EDGE>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, T, tokens,
-                                            states, scores, row, tags, lane);
-  else if constexpr (MODE == 1)
-    run_frames_1k<COMPARE, false, SEL, EDGE>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, T, tokens,
-                                             states, scores, row, tags, lane);
-  else
-    run_frames_multi<COMPARE, SEL>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, tokens, states,
-                                   scores, row, tags, lane);
-}
-
-// LDS of one wave: a copy of the current row chunk and the token marks.
+// LDS of one wave: a copy of the current row and the token marks.
 constexpr int kWaveLdsFloats = kChunk + kTagWords;
 constexpr size_t kWaveLdsBytes = kWaveLdsFloats * sizeof(float);
 
 // Pass 1: chain (b, j) decodes segment j of hypothesis b; j = 0 starts from states0[b] and the
-// caller's previous label (exact), j > 0 from the root with no previous label (speculative).
-// One wave per chain.
-template <int MODE, int SEL, bool FOREST>
+// caller's previous label (exact), j > 0 from a guess.  One wave per chain.
+template <bool FULL, int SEL, bool FOREST>
 __global__ void __launch_bounds__(256, 4) frames_spec_kernel(DeviceTree dt, TreePick pick, const float* __restrict__ logp,
                                                           int64_t frame_stride, int64_t row_stride,
                                                           const int32_t* __restrict__ states0,
@@ -927,23 +506,19 @@ __global__ void __launch_bounds__(256, 4) frames_spec_kernel(DeviceTree dt, Tree
     if (SEL == 2 && last0 != nullptr) last = last0[b];
   }
   if (!tree_ok) s = -1;  // an unknown tree marks every frame of the hypothesis like an invalid state
-  run_frames<false, MODE, SEL, true>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, T, tokens, states,
-                                     scores, row, tags, lane);
+  run_frames_1k<false, FULL, SEL, true>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, T, states0,
+                                        tokens, states, scores, row, tags, lane);
 }
 
 // Pass 2: one workgroup per hypothesis; its waves share the segments j = 1 .. nseg-1.
-//   (a) segment j is re-run from the outcome pass 1 left at the end of segment j-1 (end state and,
-//       under the CTC rule, last label) until the stored trajectory is met;
-//   (b) the outcome at the end of segment j-1 is then compared, for all segments at once, with the
-//       one segment j was re-run from, and the stale segments are re-run, in parallel rounds.
-template <int MODE, int SEL, bool FOREST>
-__global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, TreePick pick, const float* __restrict__ logp,
+template <bool FULL, int SEL, bool FOREST>
+__global__ void __launch_bounds__(512) frames_fix_kernel(DeviceTree dt, TreePick pick, const float* __restrict__ logp,
                                                           int64_t frame_stride, int64_t row_stride, float alpha, int T,
                                                           int B, int seg_len, int nseg, int32_t* __restrict__ tokens,
                                                           int32_t* __restrict__ states, float* __restrict__ scores) {
   extern __shared__ float lds[];
   __shared__ int assumed[64], assumed_tok[64];
-  __shared__ unsigned bad_lo, bad_hi;
+  __shared__ unsigned bad_words[2];
   const int lane = threadIdx.x & 63, wave = uniform_i(threadIdx.x >> 6), nwaves = blockDim.x >> 6;
   const int b = blockIdx.x;
   float* row = lds + wave * kWaveLdsFloats;
@@ -953,73 +528,16 @@ __global__ void __launch_bounds__(1024) frames_fix_kernel(DeviceTree dt, TreePic
     if (!pick_tree(pick, b, mine)) return;  // pass 1 has marked every frame of this hypothesis (the whole workgroup leaves)
   }
   const TreeView t = make_view(mine);
-  auto rerun = [&](int seg, int s, int last) {
-    const int f0 = seg * seg_len, f1 = min(T, f0 + seg_len);
-    run_frames<true, MODE, SEL>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, T, tokens, states, scores,
-                                row, tags, lane);
-  };
-  auto end_word_of = [&](int seg) {  // state word of the last frame of segment `seg` (boundary bit included)
-    const int32_t* p = states + static_cast<size_t>((seg + 1) * seg_len - 1) * B + b;
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  };
-  auto end_token_of = [&](int seg) {  // label of the last frame of segment `seg`
-    if (SEL != 2) return -1;
-    const int32_t* p = tokens + static_cast<size_t>((seg + 1) * seg_len - 1) * B + b;
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  };
-  for (int seg = 1 + wave; seg < nseg; seg += nwaves) {
-    // consumed inside rerun, after its row loads are on their way
-    const int word = end_word_of(seg - 1), last = end_token_of(seg - 1);
-    const int s = plain_state(word);
-    if (lane == 0) {
-      assumed[seg] = s;
-      assumed_tok[seg] = last;
-    }
-    // pass 1 started the segment from a guess; where its neighbour has found the guess right there is
-    // nothing to do, elsewhere the segment is re-run until it meets what is stored
-    if (uniform_i(word) < 0 || (uniform_i(word) & kGuessOk) == 0) rerun(seg, s, last);
-  }
-  // (b) rounds: wave 0 compares the outcome at the end of every segment j-1 with what segment j was last
-  // re-run from and publishes the set of stale segments; the waves re-run those in parallel from the
-  // current outcomes.  Segment 0 is exact, so after round r the segments up to r + 1 are final: at most
-  // nseg rounds, in practice one or two.
-  for (;;) {
-    __threadfence_block();
-    __syncthreads();
-    if (wave == 0) {
-      const bool check = lane >= 1 && lane < nseg;
-      const int have = check ? plain_state(end_word_of(lane - 1)) : 0;
-      const int have_tok = check ? end_token_of(lane - 1) : 0;
-      const bool stale = check && (have != assumed[lane] || (SEL == 2 && have_tok != assumed_tok[lane]));
-      if (stale) {
-        assumed[lane] = have;
-        assumed_tok[lane] = have_tok;
-      }
-      const u64 bad = __ballot(stale);
-      if (lane == 0) {
-        bad_lo = static_cast<unsigned>(bad);
-        bad_hi = static_cast<unsigned>(bad >> 32);
-      }
-    }
-    __syncthreads();
-    u64 bad = (static_cast<u64>(bad_hi) << 32) | bad_lo;
-    if (bad == 0) break;
-    for (int k = 0; bad != 0; ++k) {  // the k-th stale segment goes to wave k mod nwaves
-      const int seg = first_lane(bad);
-      bad &= bad - 1;
-      if (k % nwaves == wave) rerun(seg, assumed[seg], assumed_tok[seg]);
-    }
-  }
-  // every re-run is done: the boundary bits of pass 1 leave the output
-  if (wave == 0 && lane < nseg - 1) {
-    int32_t* p = states + static_cast<size_t>((lane + 1) * seg_len - 1) * B + b;
-    const int word = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (word >= 0 && (word & kGuessOk) != 0) *p = word & ~kGuessOk;
-  }
+  fix_segments<SEL == 2>(T, B, b, seg_len, nseg, tokens, states, assumed, assumed_tok, bad_words, lane, wave, nwaves,
+                         [&](int seg, int s, int last) {
+                           const int f0 = seg * seg_len, f1 = min(T, f0 + seg_len);
+                           run_frames_1k<true, FULL, SEL, false>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s,
+                                                                 last, T, nullptr, tokens, states, scores, row, tags, lane);
+                         });
 }
 
 // Single step: one wave per hypothesis, no speculation.  With a table of trees every hypothesis names its own.
-template <int MODE, int SEL>
+template <bool FULL, int SEL>
 __global__ void __launch_bounds__(256) step_wave_kernel(DeviceTree dt, TreePick pick, const float* __restrict__ logp,
                                                         int64_t row_stride, const int32_t* __restrict__ states_in,
                                                         const int32_t* __restrict__ last_in, float alpha, int B,
@@ -1037,8 +555,8 @@ __global__ void __launch_bounds__(256) step_wave_kernel(DeviceTree dt, TreePick 
   const int s = tree_ok ? states_in[b] : -1;  // an unknown tree marks the hypothesis like an invalid state
   int last = -1;
   if (SEL == 2 && last_in != nullptr) last = last_in[b];
-  run_frames<false, MODE, SEL>(t, logp, 0, row_stride, alpha, B, b, 0, 1, s, last, 1, tokens, states_out, scores, row,
-                               tags, lane);
+  run_frames_1k<false, FULL, SEL, false>(t, logp, 0, row_stride, alpha, B, b, 0, 1, s, last, 1, nullptr, tokens,
+                                         states_out, scores, row, tags, lane);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1121,6 +639,12 @@ __global__ void __launch_bounds__(64 * kBeamWaveMaxK) beam_wave_kernel(
       tv[4 * i + k] = (FULL || v0 + k < V) ? __fadd_rn(hs, expansion) : -INFINITY;
     }
   }
+  if (t.eos >= 0) {  // EOS rule (Sec. II-C): boosted by the value tabulated for the state; no arc carries the token
+    const float ce = __fmul_rn(alpha, cur.eos_boost);
+    const int ln = opaque(lane);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) tv[j] = slot_is(j, ln, t.eos) ? __fadd_rn(hs, __fadd_rn(x[j], ce)) : tv[j];
+  }
   // ---- the row's best totals, in order ---------------------------------------------------------------
   const int rounds = min(K, V);
   for (int r = 0; r < rounds; ++r) {
@@ -1129,8 +653,8 @@ __global__ void __launch_bounds__(64 * kBeamWaveMaxK) beam_wave_kernel(
     for (int i = 0; i < 4; ++i) g[i] = max4(tv[4 * i], tv[4 * i + 1], tv[4 * i + 2], tv[4 * i + 3]);
     const float M = ukey_val(wave_max_u(ukey(max4(g[0], g[1], g[2], g[3]))));
     const int v = uniform_i(first_token_equal(tv, g, M, lane));
-    int nx = s;  // the blank keeps the state
-    if (v != t.blank) nx = tag_test(tags, v) ? ov_next[v] : t.root_next[v];
+    int nx = s;  // the blank and the EOS keep the state
+    if (v != t.blank && v != t.eos) nx = tag_test(tags, v) ? ov_next[v] : t.root_next[v];
     if (lane == 0) {  // `rounds` entries per wave, packed
       cand_val[wave * rounds + r] = M;
       cand_idx[wave * rounds + r] = wave * V + v;
@@ -1162,8 +686,6 @@ __global__ void __launch_bounds__(64 * kBeamWaveMaxK) beam_wave_kernel(
   }
 }
 
-inline int mode_of(int V) { return V == kChunk ? 0 : (V < kChunk ? 1 : 2); }
-
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 int g_fix_waves = 8;  // waves per fix-up workgroup the device's LDS allows, set once
@@ -1171,35 +693,46 @@ int g_fix_waves = 8;  // waves per fix-up workgroup the device's LDS allows, set
 }  // namespace
 
 bool wave_path_ok(const DeviceTree& t, const float* d_logp, int64_t frame_stride, int64_t row_stride) {
-  // (the EOS rule needs the maximum of the whole boost row: such trees take the workgroup-per-row kernel)
-  return t.eos_id < 0 && t.p_root != nullptr && t.root_rec != nullptr && t.vocab_size % 4 == 0 && row_stride % 4 == 0 &&
-         frame_stride % 4 == 0 && aligned16(d_logp) && aligned16(t.root_score);
+  return t.p_root != nullptr && t.root_rec != nullptr && t.vocab_size % 4 == 0 && t.vocab_size <= kWideMaxV &&
+         row_stride % 4 == 0 && frame_stride % 4 == 0 && aligned16(d_logp) && aligned16(t.root_score);
 }
 
-// Expands to one launch per (MODE, SEL) pair; `mode` and `sel` are runtime values in 0..2.
-#define PB_DISPATCH(mode, sel, LAUNCH) \
-  switch ((mode) * 3 + (sel)) {        \
-    case 0: LAUNCH(0, 0); break;       \
-    case 1: LAUNCH(0, 1); break;       \
-    case 2: LAUNCH(0, 2); break;       \
-    case 3: LAUNCH(1, 0); break;       \
-    case 4: LAUNCH(1, 1); break;       \
-    case 5: LAUNCH(1, 2); break;       \
-    case 6: LAUNCH(2, 0); break;       \
-    case 7: LAUNCH(2, 1); break;       \
-    default: LAUNCH(2, 2); break;      \
+SegPlan plan_segments(int32_t T, int32_t B, int target_chains) {
+  // Segments: enough concurrent chains to cover the memory latency, at most kMaxSegments per
+  // hypothesis, at least kMinSegLen frames long.
+  int nseg = (target_chains + B - 1) / B;
+  nseg = nseg < 1 ? 1 : (nseg > kMaxSegments ? kMaxSegments : nseg);
+  int seg_len = (T + nseg - 1) / nseg;
+  if (seg_len < kMinSegLen) seg_len = kMinSegLen;
+  nseg = (T + seg_len - 1) / seg_len;
+  return SegPlan{nseg, seg_len};
+}
+
+// Expands to one launch per (row shape, selection rule) pair; FULL: V == 1024, `sel` a runtime value in 0..2.
+#define PB_DISPATCH(full, sel, LAUNCH)   \
+  switch ((full ? 0 : 3) + (sel)) {      \
+    case 0: LAUNCH(true, 0); break;      \
+    case 1: LAUNCH(true, 1); break;      \
+    case 2: LAUNCH(true, 2); break;      \
+    case 3: LAUNCH(false, 0); break;     \
+    case 4: LAUNCH(false, 1); break;     \
+    default: LAUNCH(false, 2); break;    \
   }
 
 int launch_step_wave(const DeviceTree& t, const TreePick& pick, const float* d_logp, int64_t row_stride,
                      const int32_t* d_states_in, const int32_t* d_last, float alpha, int32_t B, int sel, int32_t* d_tokens, int32_t* d_states_out,
                      float* d_scores, hipStream_t stream) {
+  if (t.vocab_size > kChunk)
+    return launch_step_wide(t, pick, d_logp, row_stride, d_states_in, d_last, alpha, B, sel, d_tokens, d_states_out,
+                            d_scores, stream);
   const int waves = B >= 1024 ? 4 : 1;  // few rows: spread them over as many CUs as possible
   const dim3 grid(static_cast<unsigned>((B + waves - 1) / waves)), block(static_cast<unsigned>(64 * waves));
   const size_t lds = static_cast<size_t>(waves) * kWaveLdsBytes;
-#define PB_LAUNCH(MODE, SEL)                                                                                      \
-  hipLaunchKernelGGL((step_wave_kernel<MODE, SEL>), grid, block, lds, stream, t, pick, d_logp, row_stride,       \
+  const bool full = t.vocab_size == kChunk;
+#define PB_LAUNCH(FULL, SEL)                                                                                      \
+  hipLaunchKernelGGL((step_wave_kernel<FULL, SEL>), grid, block, lds, stream, t, pick, d_logp, row_stride,       \
                      d_states_in, d_last, alpha, B, d_tokens, d_states_out, d_scores)
-  PB_DISPATCH(mode_of(t.vocab_size), sel, PB_LAUNCH)
+  PB_DISPATCH(full, sel, PB_LAUNCH)
 #undef PB_LAUNCH
   return hipGetLastError() == hipSuccess ? PB_OK : PB_EHIP;
 }
@@ -1208,30 +741,28 @@ int launch_frames_wave(const DeviceTree& t, const TreePick& pick, const float* d
                        int64_t row_stride,
                        const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B, int sel,
                        int32_t* d_tokens, int32_t* d_states, float* d_scores, hipStream_t stream) {
-  // Segments: enough concurrent chains to cover the memory latency, at most kMaxSegments per
-  // hypothesis, at least kMinSegLen frames long.
-  int nseg = (kTargetChains + B - 1) / B;
-  nseg = nseg < 1 ? 1 : (nseg > kMaxSegments ? kMaxSegments : nseg);
-  int seg_len = (T + nseg - 1) / nseg;
-  if (seg_len < kMinSegLen) seg_len = kMinSegLen;
-  nseg = (T + seg_len - 1) / seg_len;
+  if (t.vocab_size > kChunk)
+    return launch_frames_wide(t, pick, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, sel, d_tokens,
+                              d_states, d_scores, stream);
+  const SegPlan plan = plan_segments(T, B, kTargetChains);
+  const int nseg = plan.nseg, seg_len = plan.seg_len;
   const int64_t chains = static_cast<int64_t>(B) * nseg;
   const int waves = 4;
   const int64_t blocks = (chains + waves - 1) / waves;
   if (blocks > INT32_MAX) return PB_EUNSUPPORTED;
   const size_t lds = static_cast<size_t>(waves) * kWaveLdsBytes;
-  const int mode = mode_of(t.vocab_size);
+  const bool full = t.vocab_size == kChunk;
   const bool forest = pick.table != nullptr;
-#define PB_SPEC(MODE, SEL, FOREST)                                                                                   \
-  hipLaunchKernelGGL((frames_spec_kernel<MODE, SEL, FOREST>), dim3(static_cast<unsigned>(blocks)), dim3(64 * waves), \
+#define PB_SPEC(FULL, SEL, FOREST)                                                                                   \
+  hipLaunchKernelGGL((frames_spec_kernel<FULL, SEL, FOREST>), dim3(static_cast<unsigned>(blocks)), dim3(64 * waves), \
                      lds, stream, t, pick, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B,        \
                      seg_len, nseg, d_tokens, d_states, d_scores)
-#define PB_LAUNCH(MODE, SEL) PB_SPEC(MODE, SEL, false)
-#define PB_LAUNCH_F(MODE, SEL) PB_SPEC(MODE, SEL, true)
+#define PB_LAUNCH(FULL, SEL) PB_SPEC(FULL, SEL, false)
+#define PB_LAUNCH_F(FULL, SEL) PB_SPEC(FULL, SEL, true)
   if (forest) {
-    PB_DISPATCH(mode, sel, PB_LAUNCH_F)
+    PB_DISPATCH(full, sel, PB_LAUNCH_F)
   } else {
-    PB_DISPATCH(mode, sel, PB_LAUNCH)
+    PB_DISPATCH(full, sel, PB_LAUNCH)
   }
 #undef PB_LAUNCH
 #undef PB_LAUNCH_F
@@ -1240,16 +771,16 @@ int launch_frames_wave(const DeviceTree& t, const TreePick& pick, const float* d
   if (nseg > 1) {
     int fw = nseg - 1 < g_fix_waves ? nseg - 1 : g_fix_waves;
     const size_t lds2 = static_cast<size_t>(fw) * kWaveLdsBytes;
-#define PB_FIX(MODE, SEL, FOREST)                                                                                     \
-  hipLaunchKernelGGL((frames_fix_kernel<MODE, SEL, FOREST>), dim3(static_cast<unsigned>(B)), dim3(64 * fw), lds2,     \
+#define PB_FIX(FULL, SEL, FOREST)                                                                                     \
+  hipLaunchKernelGGL((frames_fix_kernel<FULL, SEL, FOREST>), dim3(static_cast<unsigned>(B)), dim3(64 * fw), lds2,     \
                      stream, t, pick, d_logp, frame_stride, row_stride, alpha, T, B, seg_len, nseg, d_tokens,         \
                      d_states, d_scores)
-#define PB_LAUNCH(MODE, SEL) PB_FIX(MODE, SEL, false)
-#define PB_LAUNCH_F(MODE, SEL) PB_FIX(MODE, SEL, true)
+#define PB_LAUNCH(FULL, SEL) PB_FIX(FULL, SEL, false)
+#define PB_LAUNCH_F(FULL, SEL) PB_FIX(FULL, SEL, true)
     if (forest) {
-      PB_DISPATCH(mode, sel, PB_LAUNCH_F)
+      PB_DISPATCH(full, sel, PB_LAUNCH_F)
     } else {
-      PB_DISPATCH(mode, sel, PB_LAUNCH)
+      PB_DISPATCH(full, sel, PB_LAUNCH)
     }
 #undef PB_LAUNCH
 #undef PB_LAUNCH_F
@@ -1285,16 +816,16 @@ int prepare_wave_kernels() {
   if (hipGetDevice(&dev) != hipSuccess) return PB_EHIP;
   if (hipDeviceGetAttribute(&max_lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return PB_EHIP;
   int waves = (max_lds - 1024) / static_cast<int>(kWaveLdsBytes);
-  waves = waves > 16 ? 16 : (waves < 1 ? 1 : waves);
+  waves = waves > 8 ? 8 : (waves < 1 ? 1 : waves);  // 8 waves per workgroup leave each wave 256 registers
   constexpr int kPlainLimit = 64 * 1024 - 1024;  // static LDS of the kernel included
   if (waves * static_cast<int>(kWaveLdsBytes) > kPlainLimit) {
     const int bytes = waves * static_cast<int>(kWaveLdsBytes);
     const hipFuncAttribute attr = hipFuncAttributeMaxDynamicSharedMemorySize;
     bool ok = true;
-#define PB_SET(MODE, SEL)                                                                                              \
-  ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(frames_fix_kernel<MODE, SEL, false>), attr, bytes) == hipSuccess && \
-       hipFuncSetAttribute(reinterpret_cast<const void*>(frames_fix_kernel<MODE, SEL, true>), attr, bytes) == hipSuccess
-    for (int ms = 0; ms < 9; ++ms) PB_DISPATCH(ms / 3, ms % 3, PB_SET)
+#define PB_SET(FULL, SEL)                                                                                              \
+  ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(frames_fix_kernel<FULL, SEL, false>), attr, bytes) == hipSuccess && \
+       hipFuncSetAttribute(reinterpret_cast<const void*>(frames_fix_kernel<FULL, SEL, true>), attr, bytes) == hipSuccess
+    for (int ms = 0; ms < 6; ++ms) PB_DISPATCH(ms < 3, ms % 3, PB_SET)
 #undef PB_SET
     if (!ok) {
       (void)hipGetLastError();
@@ -1313,7 +844,7 @@ int prepare_wave_kernels() {
     else
       (void)hipGetLastError();
   }
-  return PB_OK;
+  return prepare_wide_kernels(max_lds);
 }
 
 }  // namespace pb

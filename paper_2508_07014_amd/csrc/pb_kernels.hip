@@ -63,6 +63,10 @@ __device__ __forceinline__ void resolve(const DeviceTree& t, int s, float p_root
     score = 0.0f;
     next = s;
   }
+  if (v == t.eos_id) {  // EOS rule (Sec. II-C): tabulated per state by the host compiler; the state does not move
+    score = t.eos_score[s];
+    next = s;
+  }
 }
 
 __device__ __forceinline__ bool better(float a_val, int a_idx, float b_val, int b_idx) {
@@ -97,42 +101,6 @@ __device__ __forceinline__ void block_best(float& val, int& idx, float* sv, int*
       val = ov;
       idx = oi;
     }
-  }
-}
-
-// Workgroup-wide maximum of the values held by threads with `has` set; `any` tells whether there was one.
-__device__ __forceinline__ float block_max(float val, bool has, bool& any, float* sv, int* si) {
-  int idx = has ? 0 : -1;
-  block_best(val, idx, sv, si);
-  any = idx >= 0;
-  return val;
-}
-
-// EOS rule (Sec. II-C): the EOS column of a dense row is the largest score of the other tokens (the
-// blank aside) plus the final weight of an end-of-phrase state; the state does not move.
-// One workgroup per hypothesis, run after score_kernel on the rows it wrote.
-__global__ void __launch_bounds__(256) score_eos_kernel(DeviceTree t, const int32_t* __restrict__ states,
-                                                        float* __restrict__ scores, int32_t* __restrict__ next) {
-  __shared__ float sv[16];
-  __shared__ int si[16];
-  const int b = blockIdx.x;
-  const int s = states[b];
-  if (static_cast<unsigned>(s) >= static_cast<unsigned>(t.num_states)) return;
-  const int V = t.vocab_size;
-  const float* row = scores + static_cast<size_t>(b) * V;
-  float m = 0.0f;
-  bool has = false;
-  for (int v = threadIdx.x; v < V; v += blockDim.x) {
-    if (v == t.eos_id || v == t.blank_id) continue;
-    const float x = row[v];
-    if (!has || x > m) m = x;
-    has = true;
-  }
-  bool any;
-  m = block_max(m, has, any, sv, si);
-  if (threadIdx.x == 0) {
-    scores[static_cast<size_t>(b) * V + t.eos_id] = __fadd_rn(any ? m : 0.0f, t.final_score[s]);
-    if (next) next[static_cast<size_t>(b) * V + t.eos_id] = s;
   }
 }
 
@@ -230,20 +198,15 @@ __global__ void __launch_bounds__(256) score_kernel(DeviceTree t0, TreePick pick
 // own partial result; best_v < 0 if the thread saw no token.
 // Tokens equal to `excl_a` or `excl_b` are not candidates (-1 = none): the two-stage selection rules
 // bar the blank, and under the CTC rule the previous label, from the boosted re-selection.
-// With an EOS token the thread also returns the largest boost it saw among the other tokens (mx, has_mx:
-// the blank aside, excluded tokens included) and the EOS itself is left out: its score follows from the
-// maximum of the whole row and is added by the caller.
+// The EOS column, where the tree has one, comes out of `resolve` like any other token.
 template <int VEC>
 __device__ __forceinline__ void fused_row(const DeviceTree& t, const float* __restrict__ lrow, int s, float alpha,
                                           u64* row, int chunk, int excl_a, int excl_b, float& best, int& best_v,
-                                          int& best_next, float& mx, bool& has_mx) {
+                                          int& best_next) {
   const int V = t.vocab_size;
-  const int eos = t.eos_id;
   best = 0.0f;
   best_v = -1;
   best_next = s;
-  mx = 0.0f;
-  has_mx = false;
   for (int v0 = 0; v0 < V; v0 += chunk) {
     const int n = min(chunk, V - v0);
     if (v0 > 0) __syncthreads();  // everyone has read the previous chunk
@@ -266,13 +229,6 @@ __device__ __forceinline__ void fused_row(const DeviceTree& t, const float* __re
           resolve(t, s, p_root, row[i + k], v0 + i + k, rsa[k], rna[k], sc, nx);
           const float fused = __fadd_rn(lpa[k], __fmul_rn(alpha, sc));
           const int v = v0 + i + k;
-          if (eos >= 0) {
-            if (v == eos) continue;
-            if (v != t.blank_id && (!has_mx || sc > mx)) {
-              mx = sc;
-              has_mx = true;
-            }
-          }
           if (v != excl_a && v != excl_b && (best_v < 0 || fused > best)) {
             best = fused;
             best_v = v;
@@ -287,13 +243,6 @@ __device__ __forceinline__ void fused_row(const DeviceTree& t, const float* __re
         resolve(t, s, p_root, row[i], v0 + i, t.root_score[v0 + i], t.root_next[v0 + i], sc, nx);
         const float fused = __fadd_rn(lrow[v0 + i], __fmul_rn(alpha, sc));
         const int v = v0 + i;
-        if (eos >= 0) {
-          if (v == eos) continue;
-          if (v != t.blank_id && (!has_mx || sc > mx)) {
-            mx = sc;
-            has_mx = true;
-          }
-        }
         if (v != excl_a && v != excl_b && (best_v < 0 || fused > best)) {
           best = fused;
           best_v = v;
@@ -358,24 +307,10 @@ __global__ void __launch_bounds__(1024) fuse_kernel(DeviceTree t0, TreePick pick
         continue;
       }
     }
-    float best, mx;
+    float best;
     int best_v, best_next;
-    bool has_mx;
     const int excl_a = sel != 0 ? t.blank_id : -1, excl_b = sel == 2 ? last : -1;
-    fused_row<VEC>(t, lrow, s, alpha, row, chunk, excl_a, excl_b, best, best_v, best_next, mx, has_mx);
-    if (t.eos_id >= 0) {  // EOS candidate (Sec. II-C), entered by thread 0 into its partial result
-      bool any;
-      const float m = block_max(mx, has_mx, any, sv, si);
-      if (threadIdx.x == 0 && t.eos_id != excl_a && t.eos_id != excl_b) {
-        const float boost = __fadd_rn(any ? m : 0.0f, t.final_score[s]);
-        const float fe = __fadd_rn(lrow[t.eos_id], __fmul_rn(alpha, boost));
-        if (best_v < 0 || better(fe, t.eos_id, best, best_v)) {
-          best = fe;
-          best_v = t.eos_id;
-          best_next = s;
-        }
-      }
-    }
+    fused_row<VEC>(t, lrow, s, alpha, row, chunk, excl_a, excl_b, best, best_v, best_next);
     float win = best;
     int win_v = best_v;
     block_best(win, win_v, sv, si);
@@ -467,8 +402,6 @@ __global__ void __launch_bounds__(1024) beam_kernel(DeviceTree t0, TreePick pick
     const int s = states_in[h];
     const float hs = hyp[h];
     const float* lrow = logp + static_cast<size_t>(h) * row_stride;
-    float mx = 0.0f;
-    bool has_mx = false;
     for (int v0 = 0; v0 < V; v0 += chunk) {
       const int n = min(chunk, V - v0);
       __syncthreads();  // everyone has read the previous row
@@ -490,26 +423,10 @@ __global__ void __launch_bounds__(1024) beam_kernel(DeviceTree t0, TreePick pick
           float sc;
           int nx;
           resolve(t, s, p_root, row[i0 + q], v, t.root_score[v], t.root_next[v], sc, nx);
-          if (t.eos_id >= 0) {
-            if (v == t.eos_id) continue;
-            if (v != t.blank_id && (!has_mx || sc > mx)) {
-              mx = sc;
-              has_mx = true;
-            }
-          }
           const float expansion = __fadd_rn(lpa[q], __fmul_rn(alpha, sc));
           const float total = __fadd_rn(hs, expansion);
           top.push(total, k * V + v, nx);
         }
-      }
-    }
-    if (t.eos_id >= 0) {  // EOS candidate of this beam (Sec. II-C)
-      bool any;
-      const float m = block_max(mx, has_mx, any, sv, si);
-      if (threadIdx.x == 0) {
-        const float boost = __fadd_rn(any ? m : 0.0f, t.final_score[s]);
-        const float expansion = __fadd_rn(lrow[t.eos_id], __fmul_rn(alpha, boost));
-        top.push(__fadd_rn(hs, expansion), k * V + t.eos_id, s);
       }
     }
   }
@@ -525,16 +442,6 @@ __global__ void __launch_bounds__(1024) beam_kernel(DeviceTree t0, TreePick pick
       top.pop();
     }
   }
-}
-
-// ------------------------------------------------------------------------------------------------
-// Dependent-load latency probe: one lane follows table[i] for `hops` loads.  The decode recurrence
-// (state -> record -> arcs -> next state) is a chain of such loads, so this is the per-hop floor
-// of every single-step call.
-__global__ void chase_kernel(const int32_t* __restrict__ table, int32_t start, int32_t hops, int32_t* __restrict__ out) {
-  int32_t i = start + static_cast<int32_t>(threadIdx.x);  // launched with one thread; keeps the loads on the vector path
-  for (int32_t h = 0; h < hops; ++h) i = table[i];
-  *out = i;
 }
 
 inline int pick_chunk(int V) { return V < kMaxChunk ? ((V + 3) & ~3) : kMaxChunk; }
@@ -569,9 +476,6 @@ int launch_score(const DeviceTree& t, const TreePick& pick, const int32_t* d_sta
   else
     hipLaunchKernelGGL(score_kernel<1>, grid, dim3(256), lds, stream, t, pick, d_states, B, d_scores, d_next, tile,
                        tiles, per);
-  if (t.eos_id >= 0)
-    hipLaunchKernelGGL(score_eos_kernel, dim3(static_cast<unsigned>(B)), dim3(256), 0, stream, t, d_states, d_scores,
-                       d_next);
   return check_launch();
 }
 
@@ -589,11 +493,6 @@ int launch_fuse(const DeviceTree& t, const TreePick& pick, const float* d_logp, 
   else
     hipLaunchKernelGGL(fuse_kernel<1>, grid, block, lds, stream, t, pick, d_logp, frame_stride, row_stride, d_states0, d_last0,
                        alpha, T, B, sel, d_tokens, d_states, d_scores, chunk);
-  return check_launch();
-}
-
-int launch_chase(const int32_t* d_table, int32_t start, int32_t hops, int32_t* d_out, hipStream_t stream) {
-  hipLaunchKernelGGL(chase_kernel, dim3(1), dim3(1), 0, stream, d_table, start, hops, d_out);
   return check_launch();
 }
 

@@ -35,7 +35,26 @@ constexpr int kTargetChains = PB_TARGET_CHAINS;  // concurrent decode chains aim
 constexpr int kMinSegLen = 8;        // shortest speculative segment, in frames
 constexpr int kMaxSegments = 64;     // segments per hypothesis (one lane each in the validation pass)
 
+constexpr int kWideMaxV = 16384;     // widest row of the wave kernels (the root scores of a row live in LDS)
+#ifndef PB_WIDE_TARGET_CHAINS
+#define PB_WIDE_TARGET_CHAINS 2048
+#endif
+constexpr int kWideTargetChains = PB_WIDE_TARGET_CHAINS;  // the same for rows wider than 1024 tokens
+
+struct SegPlan {
+  int nseg, seg_len;
+};
+SegPlan plan_segments(int32_t T, int32_t B, int target_chains);
+
 bool wave_path_ok(const DeviceTree& t, const float* d_logp, int64_t frame_stride, int64_t row_stride);
+// Rows wider than 1024 tokens (pb_wide.hip); same arguments as the calls below, which forward to them.
+int prepare_wide_kernels(int max_lds_bytes);
+int launch_step_wide(const DeviceTree& t, const TreePick& pick, const float* d_logp, int64_t row_stride,
+                     const int32_t* d_states_in, const int32_t* d_last, float alpha, int32_t B, int sel,
+                     int32_t* d_tokens, int32_t* d_states_out, float* d_scores, hipStream_t stream);
+int launch_frames_wide(const DeviceTree& t, const TreePick& pick, const float* d_logp, int64_t frame_stride,
+                       int64_t row_stride, const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T,
+                       int32_t B, int sel, int32_t* d_tokens, int32_t* d_states, float* d_scores, hipStream_t stream);
 int prepare_wave_kernels();  // once per device, after the device has been made current
 int launch_step_wave(const DeviceTree& t, const TreePick& pick, const float* d_logp, int64_t row_stride,
                      const int32_t* d_states_in,
@@ -45,9 +64,6 @@ int launch_frames_wave(const DeviceTree& t, const TreePick& pick, const float* d
                        int64_t row_stride,
                        const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B, int sel,
                        int32_t* d_tokens, int32_t* d_states, float* d_scores, hipStream_t stream);
-
-// Latency probe: `hops` dependent loads through d_table (every entry a valid index into it).
-int launch_chase(const int32_t* d_table, int32_t start, int32_t hops, int32_t* d_out, hipStream_t stream);
 
 // Wave-per-beam kernel (pb_frames.hip): rows as for the wave path, V <= 1024 and a beam the LDS can hold.
 bool beam_wave_ok(const DeviceTree& t, const float* d_logp, int64_t row_stride, int32_t K);

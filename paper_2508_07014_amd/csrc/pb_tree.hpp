@@ -31,7 +31,8 @@ struct alignas(32) RootRec {
   int32_t fail;
   float backoff;
   float p_root;       // ... and its total backoff down to the root
-  int32_t pad0, pad1;
+  float eos_score;    // ... and its EOS boost (0 without an EOS rule)
+  int32_t pad;
 };
 
 // Device mirror (one allocation, sub-arrays aligned to 256 bytes).
@@ -42,7 +43,8 @@ struct DeviceTree {
   const int32_t* root_next = nullptr;  // [V]
   const float* p_root = nullptr;       // [N] backoff accumulated from the state down to the root (fp32, chain order)
   const RootRec* root_rec = nullptr;   // [V]
-  const float* final_score = nullptr;  // [N] final weight of the EOS rule (0 for states that end no phrase); null without EOS
+  const float* eos_score = nullptr;    // [N] boost of the EOS token in every state (Sec. II-C: largest score of the other
+                                       // tokens plus the final weight of an end-of-phrase state); null without an EOS rule
   int32_t num_states = 0;
   int32_t vocab_size = 0;
   int32_t blank_id = -1;
@@ -64,7 +66,7 @@ struct HostTree {
   std::vector<ArcRec> arc;
   std::vector<RootRec> root_rec;
   std::vector<int32_t> arc_begin, arc_count, fail, depth, parent, arc_token, root_next;
-  std::vector<float> backoff, arc_score, root_score, p_root, final_score;
+  std::vector<float> backoff, arc_score, root_score, p_root, final_score, eos_score;
   std::vector<uint8_t> is_final;
   std::vector<double> acc;
 };

@@ -1,0 +1,396 @@
+// Device helpers shared by the wave-per-hypothesis kernels (gfx950, wave64): scalar-path views of the tree,
+// order-preserving keys and DPP reductions, row loads in the 16-tokens-per-lane layout, per-wave token marks.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <climits>
+#include <cmath>
+#include <cstdint>
+
+#include "pb_kernels.hpp"
+
+namespace pb {
+namespace wv {
+
+#define PB_AS4 __attribute__((address_space(4)))
+
+constexpr int kChunk = 1024;  // tokens per chunk: 16 per lane
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+using u64 = unsigned long long;
+
+// Scalar-load views: the tree is never written while kernels run, so wave-uniform reads may go
+// through the constant address space (scalar cache).
+struct TreeView {
+  const v4i PB_AS4* state;     // StateRec as four dwords: arc_begin, arc_count, fail, backoff bits
+  const float PB_AS4* p_root;
+  const int32_t PB_AS4* root_next;
+  const v8i PB_AS4* root_rec;  // RootRec as eight dwords
+  const float PB_AS4* eos_score;  // null without an EOS rule
+  const ArcRec* arc;
+  const float* root_score;
+  int num_states, V, blank, eos;
+};
+
+__device__ __forceinline__ TreeView make_view(const DeviceTree& t) {
+  TreeView v;
+  v.state = (const v4i PB_AS4*)t.state;
+  v.p_root = (const float PB_AS4*)t.p_root;
+  v.root_next = (const int32_t PB_AS4*)t.root_next;
+  v.root_rec = (const v8i PB_AS4*)t.root_rec;
+  v.eos_score = (const float PB_AS4*)t.eos_score;
+  v.arc = t.arc;
+  v.root_score = t.root_score;
+  v.num_states = t.num_states;
+  v.V = t.vocab_size;
+  v.blank = t.blank_id;
+  v.eos = t.eos_id;
+  return v;
+}
+
+// Values that are wave-uniform by construction, told to the compiler (keeps them in SGPRs and the
+// loads they address on the scalar path).
+__device__ __forceinline__ int uniform_i(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ float uniform_f(float v) {
+  return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v)));
+}
+
+// Order-preserving fp32 <-> uint32 (every real value, -inf included, maps above 0).
+__device__ __forceinline__ unsigned ukey(float f) {
+  const int b = __float_as_int(f);
+  return static_cast<unsigned>(b) ^ (static_cast<unsigned>(b >> 31) | 0x80000000u);
+}
+__device__ __forceinline__ float ukey_val(unsigned k) {
+  const unsigned m = (k & 0x80000000u) ? 0x80000000u : 0xffffffffu;
+  return __uint_as_float(k ^ m);
+}
+
+template <int CTRL>
+__device__ __forceinline__ unsigned dpp0(unsigned v) {  // lanes without a source read 0
+  return static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xf, 0xf, true));
+}
+// Wave-wide unsigned max; 0 is the identity.  The result is wave-uniform (read from lane 63).
+__device__ __forceinline__ unsigned wave_max_u(unsigned v) {
+  v = max(v, dpp0<0x111>(v));  // row_shr:1
+  v = max(v, dpp0<0x112>(v));  // row_shr:2
+  v = max(v, dpp0<0x114>(v));  // row_shr:4
+  v = max(v, dpp0<0x118>(v));  // row_shr:8
+  v = max(v, dpp0<0x142>(v));  // row_bcast:15
+  v = max(v, dpp0<0x143>(v));  // row_bcast:31
+  return static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(v), 63));
+}
+// Wave-wide min of non-negative ints (INT_MAX = nothing).
+__device__ __forceinline__ int wave_min_nn(int v) {
+  return INT_MAX - static_cast<int>(wave_max_u(static_cast<unsigned>(INT_MAX - v)));
+}
+// The lane id again, but opaque to the optimiser: values derived from it inside a rarely taken branch
+// are then computed there instead of being hoisted out of the frame loop into long-lived registers.
+__device__ __forceinline__ int opaque(int v) {
+  asm volatile("" : "+v"(v));
+  return v;
+}
+__device__ __forceinline__ int first_lane(u64 mask) { return __builtin_ctzll(mask); }
+
+__device__ __forceinline__ int tok_of(int j, int lane) { return 256 * (j >> 2) + 4 * lane + (j & 3); }
+// Does the lane's slot j hold chunk-relative token `rel` (wave-uniform)?  Written so that the slot
+// test stays on the scalar side and no per-slot token ids have to live in vector registers.
+__device__ __forceinline__ bool slot_is(int j, int lane, int rel) {
+  const int slot = ((rel >> 8) << 2) | (rel & 3);  // uniform
+  return (slot == j) && (lane == ((rel >> 2) & 63)) && (static_cast<unsigned>(rel) < static_cast<unsigned>(kChunk));
+}
+
+__device__ __forceinline__ bool valid_state(const TreeView& t, int s) {
+  return static_cast<unsigned>(s) < static_cast<unsigned>(t.num_states);
+}
+
+struct Rec {  // wave-uniform copy of a StateRec
+  int begin, count, fail;
+  float backoff;
+};
+__device__ __forceinline__ Rec load_rec(const TreeView& t, int s) {
+  const v4i r = t.state[s];
+  Rec o;
+  o.begin = r.x;
+  o.count = r.y;
+  o.fail = r.z;
+  o.backoff = __int_as_float(r.w);
+  return o;
+}
+
+struct Cursor {  // wave-uniform decoding state of one hypothesis
+  int s;
+  Rec rec;
+  float p_root;
+  float eos_boost;  // boost of the EOS token in this state (Sec. II-C); 0 without an EOS rule
+};
+__device__ __forceinline__ Cursor cursor_at(const TreeView& t, int s) {
+  Cursor c;
+  c.s = s;
+  c.rec = load_rec(t, s);
+  c.p_root = t.p_root[s];
+  c.eos_boost = 0.0f;
+  if (t.eos >= 0) c.eos_boost = t.eos_score[s];
+  return c;
+}
+__device__ __forceinline__ Cursor cursor_from_root_rec(const v8i& r) {
+  Cursor c;
+  c.s = r.s0;
+  c.rec.begin = r.s1;
+  c.rec.count = r.s2;
+  c.rec.fail = r.s3;
+  c.rec.backoff = __int_as_float(r.s4);
+  c.p_root = __int_as_float(r.s5);
+  c.eos_boost = __int_as_float(r.s6);
+  return c;
+}
+
+// Selection rule (enum pb_select_mode): 0 = single-stage fused arg-max, 1 = two-stage, 2 = two-stage
+// with the CTC repeat rule (Sec. II-C).  In the two-stage modes the blank is never a candidate of
+// the boosted re-selection: its column carries NaN, which neither fmaxf nor an equality test ever
+// selects, so an excluded token costs nothing in the reductions.
+//
+// alpha * (p_root + root_score[v]) for the lane's 16 tokens; the blank column boosts by 0 (SEL == 0)
+// or is excluded (SEL != 0).
+template <int SEL>
+__device__ __forceinline__ void make_base_boost(int cb, int lane, int blank, float p_root, float alpha,
+                                                const float (&rw)[16], float (&c)[16]) {
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    const float boost = slot_is(j, lane, blank - cb) ? (SEL == 0 ? 0.0f : NAN) : __fadd_rn(p_root, rw[j]);
+    c[j] = __fmul_rn(alpha, boost);
+  }
+}
+
+// Loads the lane's 16 values of chunk `cb` of a V-long fp32 array; positions >= V read as `fill`.
+template <bool FULL>
+__device__ __forceinline__ void load16(const float* __restrict__ base, int cb, int V, int lane, float fill,
+                                       float (&x)[16]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int v = cb + 256 * i + 4 * lane;
+    if (FULL || v < V) {  // V % 4 == 0: a 16-byte group is entirely inside or outside the row
+      const float4 q = *reinterpret_cast<const float4*>(base + v);
+      x[4 * i + 0] = q.x; x[4 * i + 1] = q.y; x[4 * i + 2] = q.z; x[4 * i + 3] = q.w;
+    } else {
+      x[4 * i + 0] = x[4 * i + 1] = x[4 * i + 2] = x[4 * i + 3] = fill;
+    }
+  }
+}
+
+__device__ __forceinline__ void store_row_lds(float* row, int lane, const float (&x)[16]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    *reinterpret_cast<float4*>(row + 256 * i + 4 * lane) = make_float4(x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]);
+}
+
+// Lowest token (chunk-relative) whose fused value equals M; g are the lane's four group maxima.
+__device__ __forceinline__ int first_token_equal(const float (&f)[16], const float (&g)[4], float M, int lane) {
+  const u64 b0 = __ballot(g[0] == M), b1 = __ballot(g[1] == M), b2 = __ballot(g[2] == M), b3 = __ballot(g[3] == M);
+  int gi;
+  u64 bm, e0, e1, e2;  // the fourth token of a group needs no ballot: it is the one left
+  if (b0) {
+    gi = 0; bm = b0;
+    e0 = __ballot(f[0] == M); e1 = __ballot(f[1] == M); e2 = __ballot(f[2] == M);
+  } else if (b1) {
+    gi = 1; bm = b1;
+    e0 = __ballot(f[4] == M); e1 = __ballot(f[5] == M); e2 = __ballot(f[6] == M);
+  } else if (b2) {
+    gi = 2; bm = b2;
+    e0 = __ballot(f[8] == M); e1 = __ballot(f[9] == M); e2 = __ballot(f[10] == M);
+  } else if (b3) {
+    gi = 3; bm = b3;
+    e0 = __ballot(f[12] == M); e1 = __ballot(f[13] == M); e2 = __ballot(f[14] == M);
+  } else {
+    return 0;  // only with NaN inputs (precondition violation): stay in range
+  }
+  const int L = first_lane(bm);
+  const u64 bit = 1ull << L;
+  const int k = (e0 & bit) ? 0 : (e1 & bit) ? 1 : (e2 & bit) ? 2 : 3;
+  return 256 * gi + 4 * L + k;
+}
+
+// Per-wave token marks: one bit per token of the current chunk (32 dwords of LDS).  LDS operations
+// of one wave execute in order, so clear -> set -> test needs no barrier inside the wave.
+constexpr int kTagWords = kChunk / 32;
+__device__ __forceinline__ void tags_clear(unsigned* bits, int lane) {
+  if (lane < kTagWords) bits[lane] = 0u;
+}
+__device__ __forceinline__ void tag_set(unsigned* bits, int tk) { atomicOr(&bits[tk >> 5], 1u << (tk & 31)); }
+__device__ __forceinline__ bool tag_test(const unsigned* bits, int tk) { return ((bits[tk >> 5] >> (tk & 31)) & 1u) != 0u; }
+
+__device__ __forceinline__ float max4(float a, float b, float c, float d) { return fmaxf(fmaxf(a, b), fmaxf(c, d)); }
+
+// Stage 1 of the two-stage rule on one chunk: the unboosted row maximum and its lowest token.
+__device__ __forceinline__ void plain_argmax(const float (&x)[16], int lane, float& M0, int& v0) {
+  float g[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) g[i] = max4(x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]);
+  M0 = ukey_val(wave_max_u(ukey(max4(g[0], g[1], g[2], g[3]))));
+  v0 = first_token_equal(x, g, M0, lane);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Multi-frame decoding in speculative segments: what the row layouts (rows of up to 1024 tokens, wider
+// rows) share.
+//
+// The T frames of a hypothesis are cut into segments decoded concurrently, one wave each (pass 1).  A
+// segment that does not begin the call starts from a guess of the state (and, under the CTC rule, of
+// the label) the frame before it ends in.  The segment on the left computes the same guess from the
+// same rows at its end and, when it equals what it really ended in, sets kGuessOk in the state word
+// it stores for its last frame.  Pass 2 re-runs the other segments from their neighbour's end state
+// until they meet the stored trajectory (a finite automaton: equal (state, label) after a frame means
+// an identical future), then compares every assumed start with the final outcome before it and re-runs
+// the stale segments in parallel rounds, and clears the bits.  States stay below 2^30 for this.
+constexpr int kGuessOk = 1 << 30;
+// Frames a boundary guess may look back over.  A frame that keeps the state (a blank, under every rule)
+// says nothing about it, so the guess goes back to the last frame that moved it.
+constexpr int kLookBack = 8;
+
+// State word of a stored frame without the boundary bit (an invalid frame holds -1 and stays as it is).
+__device__ __forceinline__ int plain_state(int word) { return word < 0 ? word : (word & ~kGuessOk); }
+
+// Outputs that other waves of the same launch may read while or after they are written (pass 2) go
+// through relaxed agent-scope atomics on both sides; the fences around the workgroup barriers order them.
+__device__ __forceinline__ int peek_i32(const int32_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void publish_i32(int32_t* p, int v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ void fill_invalid(int B, int b, int f0, int f1, int32_t* tokens, int32_t* states,
+                                             float* scores, int lane) {
+  for (int f = f0 + lane; f < f1; f += 64) {
+    const size_t o = static_cast<size_t>(f) * B + b;
+    publish_i32(tokens + o, -1);
+    publish_i32(states + o, -1);
+    scores[o] = NAN;
+  }
+}
+
+// Outputs of up to 64 consecutive frames held one per lane (frame base + l in lane l) and written
+// together, so that no store sits between the loads of the in-order memory queue.
+struct LaneOut {
+  int base, tok, st;
+  float sc;
+  __device__ __forceinline__ void put(int lane, int f, int token, int word, float val) {
+    if (lane == f - base) {
+      tok = token;
+      st = word;
+      sc = val;
+    }
+  }
+  template <bool PUBLISH>
+  __device__ __forceinline__ void flush(int lane, int count, int B, int b, int32_t* tokens, int32_t* states,
+                                        float* scores) const {
+    if (lane < count) {
+      const size_t o = static_cast<size_t>(base + lane) * B + b;
+      if (PUBLISH) {
+        publish_i32(tokens + o, tok);
+        publish_i32(states + o, st);
+      } else {
+        tokens[o] = tok;
+        states[o] = st;
+      }
+      scores[o] = sc;
+    }
+  }
+};
+
+// The stored trajectory of a range that is being re-run, one frame per lane (64 at a time), requested
+// ahead so that comparing a frame costs a lane read instead of a memory round trip.
+template <bool WITH_TOKENS>
+struct StoredLane {
+  int st, tok;
+  __device__ __forceinline__ void fetch(int lane, int fbase, int f1, int B, int b, const int32_t* tokens,
+                                        const int32_t* states) {
+    st = -1;
+    tok = -1;
+    const int f = fbase + lane;
+    if (f < f1) {
+      const size_t o = static_cast<size_t>(f) * B + b;
+      st = peek_i32(states + o);
+      if (WITH_TOKENS) tok = peek_i32(tokens + o);
+    }
+  }
+  __device__ __forceinline__ int state_at(int slot) const { return plain_state(__builtin_amdgcn_readlane(st, slot)); }
+  __device__ __forceinline__ int token_at(int slot) const { return __builtin_amdgcn_readlane(tok, slot); }
+};
+
+// Pass 2 for one hypothesis (one workgroup; its waves share the segments 1 .. nseg-1).
+//   rerun(seg, state, label): decodes segment `seg` again from that outcome until it meets what is stored.
+//   (a) every segment whose left neighbour has not certified its guess is re-run from the outcome pass 1 stored
+//       at the end of that neighbour.  Neighbours are re-run at the same time, so that outcome may be
+//       replaced meanwhile: (b) repairs it.
+//   (b) rounds: wave 0 compares the outcome at the end of every segment j-1 with what segment j was last
+//       decoded from and publishes the set of stale segments; the waves re-run those in parallel.  Segment 0
+//       is exact, so after round r the segments up to r + 1 are final: at most nseg rounds, in practice one
+//       or two.
+//   Words that cross waves are relaxed agent-scope atomics; a release fence before and an acquire fence
+//   after each workgroup barrier order them.
+template <bool WITH_TOKENS, typename Rerun>
+__device__ __forceinline__ void fix_segments(int T, int B, int b, int seg_len, int nseg, int32_t* tokens,
+                                             int32_t* states, int* assumed, int* assumed_tok, unsigned* bad_words,
+                                             int lane, int wave, int nwaves, Rerun&& rerun) {
+  auto end_word_of = [&](int seg) {  // state word of the last frame of segment `seg` (boundary bit included)
+    return peek_i32(states + static_cast<size_t>((seg + 1) * seg_len - 1) * B + b);
+  };
+  auto end_token_of = [&](int seg) {  // label of the last frame of segment `seg`
+    if (!WITH_TOKENS) return -1;
+    return peek_i32(tokens + static_cast<size_t>((seg + 1) * seg_len - 1) * B + b);
+  };
+  {
+    // every wave reads the outcome before every segment in one access (lane j: the end of segment j - 1) and
+    // records, for its own segments, exactly the value it decides with
+    const bool has = lane >= 1 && lane < nseg;
+    const int words = has ? end_word_of(lane - 1) : -1;
+    const int labels = has ? end_token_of(lane - 1) : -1;
+    for (int seg = 1 + wave; seg < nseg; seg += nwaves) {
+      const int word = __builtin_amdgcn_readlane(words, seg), last = __builtin_amdgcn_readlane(labels, seg);
+      const int s = plain_state(word);
+      if (lane == 0) {
+        assumed[seg] = s;
+        assumed_tok[seg] = last;
+      }
+      if (word < 0 || (word & kGuessOk) == 0) rerun(seg, s, last);
+    }
+  }
+  for (;;) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    if (wave == 0) {
+      const bool check = lane >= 1 && lane < nseg;
+      const int have = check ? plain_state(end_word_of(lane - 1)) : 0;
+      const int have_tok = check ? end_token_of(lane - 1) : 0;
+      const bool stale = check && (have != assumed[lane] || (WITH_TOKENS && have_tok != assumed_tok[lane]));
+      if (stale) {
+        assumed[lane] = have;
+        assumed_tok[lane] = have_tok;
+      }
+      const u64 bad = __ballot(stale);
+      if (lane == 0) {
+        bad_words[0] = static_cast<unsigned>(bad);
+        bad_words[1] = static_cast<unsigned>(bad >> 32);
+      }
+    }
+    __syncthreads();
+    u64 bad = (static_cast<u64>(bad_words[1]) << 32) | bad_words[0];
+    if (bad == 0) break;
+    for (int k = 0; bad != 0; ++k) {  // the k-th stale segment goes to wave k mod nwaves
+      const int seg = first_lane(bad);
+      bad &= bad - 1;
+      if (k % nwaves == wave) rerun(seg, assumed[seg], assumed_tok[seg]);
+    }
+  }
+  // every re-run is done: the boundary bits of pass 1 leave the output
+  if (wave == 0 && lane < nseg - 1) {
+    int32_t* p = states + static_cast<size_t>((lane + 1) * seg_len - 1) * B + b;
+    const int word = peek_i32(p);
+    if (word >= 0 && (word & kGuessOk) != 0) publish_i32(p, word & ~kGuessOk);
+  }
+}
+
+}  // namespace wv
+}  // namespace pb

@@ -197,6 +197,52 @@ def test_eos_options_are_validated_and_reported():
     assert pb.pb_info(pb.pb_build(toks, offs, 6, 0, device=-1))["eos_id"] == -1
 
 
+@pytest.mark.parametrize("seed", range(40))
+def test_eos_table_equals_the_oracles_row_maximum(seed):
+    """The host compiler tabulates the EOS boost per state; the oracle finds it by looping over every other
+    token of the state's row (Sec. II-C).  Tiny trees with mixed weights, c_unk != 0 and both weight modes."""
+    rng = np.random.Generator(np.random.PCG64(4000 + seed))
+    V = int(rng.integers(4, 9))
+    blank = 0 if seed % 3 else -1
+    toks, offs, w = W.tiny_case(4100 + seed, vocab_size=V - 1, blank_id=blank)   # the last id stays free for the EOS
+    eos = V - 1
+    kw = dict(weights=w * rng.choice([-1.0, 1.0], size=len(w)).astype(np.float32), weight_mode=seed % 3,
+              unk_score=float(rng.integers(-2, 3)) * 0.5)
+    fin = float(rng.integers(0, 4)) * 0.25
+    tr = pb.pb_build(toks, offs, V, blank, device=-1, eos_id=eos, final_eos_score=fin, **kw)
+    ot = OracleTree(toks, offs, V, blank, eos_id=eos, final_eos_score=fin, **kw)
+    table = pb.pb_host_arrays(tr)["eos_score"]
+    want = ot.score(np.arange(ot.num_states, dtype=np.int32))[0][:, eos]
+    assert np.array_equal(table, want)
+    assert pb.pb_host_arrays(pb.pb_build(toks, offs, V, blank, device=-1, **kw))["eos_score"] is None
+
+
+def test_validate_accepts_compiled_trees_and_flags_planted_damage(monkeypatch):
+    """pb_validate bounds-checks the compiled arrays; a mistake planted in the tree's own host arrays (through
+    the view pointers) must be reported as PB_ERANGE.  PB_DEBUG=1 makes pb_build run the check itself."""
+    cfg = W.CONFIGS[2]
+    toks, offs = W.make_phrases(cfg)
+    toks = np.where(toks == cfg.vocab_size - 1, 1, toks).astype(np.int32)   # the last id becomes the EOS
+    tr = pb.pb_build(toks, offs, cfg.vocab_size, cfg.blank_id, device=-1, eos_id=cfg.vocab_size - 1)
+    assert pb.pb_validate(tr) == pb.PB_OK
+    view = pb.binding.pb_host_view()
+    assert pb.load().pb_host_arrays(tr.handle, C.byref(view)) == 0
+    n = pb.pb_info(tr)["num_states"]
+    for name, idx, bad in (("fail", n // 2, n + 5), ("arc_count", 7, 10 ** 6), ("arc_token", 3, cfg.vocab_size),
+                           ("root_next", 5, -3), ("arc_begin", n - 1, n + 1)):
+        ptr = getattr(view, name)
+        keep = ptr[idx]
+        ptr[idx] = bad
+        assert pb.pb_validate(tr) == pb.PB_ERANGE, name
+        ptr[idx] = keep
+        assert pb.pb_validate(tr) == pb.PB_OK
+    assert pb.pb_validate_states(tr, [0, 5, n - 1]) == -1
+    assert pb.pb_validate_states(tr, [0, 5, n, -1]) == 2
+    assert pb.pb_validate_states(tr, [-1]) == 0
+    monkeypatch.setenv("PB_DEBUG", "1")
+    assert pb.pb_validate(pb.pb_build(toks, offs, cfg.vocab_size, cfg.blank_id, device=-1)) == pb.PB_OK
+
+
 def test_host_compiler_is_clean_under_address_and_ub_sanitizers(tmp_path):
     """tests/host_compile_sanitized.cpp: the compiler alone (no HIP runtime) built with g++ -fsanitize."""
     import shutil
