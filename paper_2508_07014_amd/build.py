@@ -8,7 +8,8 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
-LIB = os.path.join(PKG, "libpb.so")
+# (PB_LIBRARY: load another build of the library, e.g. one compiled with different tuning constants for a sweep)
+LIB = os.environ.get("PB_LIBRARY") or os.path.join(PKG, "libpb.so")
 PROBE_LIB = os.path.join(PKG, "libpb_probe.so")  # measurement probes of bench.py, not part of the product library
 SOURCES = ["pb_compile.cpp", "pb_kernels.hip", "pb_frames.hip", "pb_wide.hip", "pb_api.hip"]
 HEADERS = ["pb_tree.hpp", "pb_kernels.hpp", "pb_wave.hpp", os.path.join(ROOT, "include", "pb.h")]

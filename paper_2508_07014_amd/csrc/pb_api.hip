@@ -393,8 +393,10 @@ int pb_validate(const pb_tree* tree) {
     // failure links lead to strictly shallower states, so every chain ends in the root
     if (!in(h.fail[s], 0, N) || (s > 0 && h.depth[h.fail[s]] >= h.depth[s]) || (s == 0 && h.fail[s] != 0)) return PB_ERANGE;
     const pb::StateRec& r = h.state[s];
-    if (r.arc_begin != h.arc_begin[s] || r.arc_count != h.arc_count[s] || r.fail != h.fail[s] ||
-        r.backoff != h.backoff[s])
+    const int32_t f = h.fail[s];
+    if (r.arc_begin != h.arc_begin[s] || r.arc_count != h.arc_count[s] || r.fail != f || r.backoff != h.backoff[s] ||
+        r.f_arc_begin != h.arc_begin[f] || r.f_arc_count != h.arc_count[f] || r.f_fail != h.fail[f] ||
+        r.f_backoff != h.backoff[f])
       return PB_ERANGE;
   }
   if (next_arc != A) return PB_ERANGE;

@@ -232,7 +232,10 @@ int compile_tree(const int32_t* tokens, const int64_t* offsets, int64_t n_phrase
       }
     }
     t.state.resize(N);
-    for (int32_t s = 0; s < N; ++s) t.state[s] = {t.arc_begin[s], t.arc_count[s], t.fail[s], t.backoff[s]};
+    for (int32_t s = 0; s < N; ++s) {
+      const int32_t f = t.fail[s];
+      t.state[s] = {t.arc_begin[s], t.arc_count[s], f, t.backoff[s], t.arc_begin[f], t.arc_count[f], t.fail[f], t.backoff[f]};
+    }
     t.root_rec.resize(V);
     for (int32_t v = 0; v < V; ++v) {
       const int32_t n = t.root_next[v];

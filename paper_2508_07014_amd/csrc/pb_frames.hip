@@ -51,6 +51,13 @@ namespace {
 
 using namespace wv;
 
+#ifdef PB_STATS  // development build: counters of the fix-up pass (re-runs, frames re-run, re-runs that reached their end)
+__device__ unsigned long long g_stats[8];
+#define PB_STAT(i, v) do { if (lane == 0) atomicAdd(&g_stats[i], static_cast<unsigned long long>(v)); } while (0)
+#else
+#define PB_STAT(i, v) do { } while (0)
+#endif
+
 // ------------------------------------------------------------------------------------------------
 // Base boosts of a row with V <= 1024 for the lane's 16 tokens; the root scores come from memory
 // (cache-resident) because they are needed only when the accumulated backoff of the state changes.
@@ -71,7 +78,7 @@ __device__ __forceinline__ void rebuild_base_boost(const TreeView& t, int lane, 
 //   row / tags  this wave's LDS copy of the row and its token marks
 //   last  label of the previous frame (SEL == 2 only; any value outside [0, V) = none)
 //   need_record  false when no frame follows: the record of the next state is then not fetched
-template <bool FULL, int SEL, int EARLY, typename NextRow>
+template <bool FULL, int SEL, int EARLY, int EARLY1, int GROUP, typename NextRow>
 __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const float (&x)[16], float (&c)[16],
                                          float& c_p, float alpha, float* row, unsigned* tags, int lane, int last,
                                          bool need_record, NextRow&& next_row, float& out_val, int& out_tok,
@@ -91,6 +98,15 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
   ArcRec early[kEarly];
 #pragma unroll
   for (int q = 0; q < kEarly; ++q) early[q] = t.arc[rec0.begin + max(0, min(64 * q + lane, rec0.count - 1))];
+  // The cursor also holds the record of the second chain state (often a depth-1 state with hundreds of arcs):
+  // its first arcs are requested here as well, when there is such a state.
+  constexpr int kEarly1 = EARLY1;
+  const Rec rec1 = cur.rec1;
+  ArcRec early1[kEarly1 > 0 ? kEarly1 : 1];
+  if (multi) {
+#pragma unroll
+    for (int q = 0; q < kEarly1; ++q) early1[q] = t.arc[rec1.begin + max(0, min(64 * q + lane, rec1.count - 1))];
+  }
   next_row();
   if constexpr (SEL != 0) {
     // stage 1: selection without boosting; a blank (or a CTC repeat) is emitted as it is
@@ -123,9 +139,9 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
   // The CTC rule bars the previous label from the re-selection.  The frame is first decided with the
   // label still in; only if it wins is the frame decided again with the label excluded (excl >= 0).
   for (int excl = -1;;) {
-    // ---- early load: record of the next chain state ----------------------------------------------
-    Rec nrec = rec0;
-    if (multi) nrec = load_rec(t, rec0.fail);
+    // ---- early load: records of the third and fourth chain state -----------------------------------
+    Rec2 nn{rec1, rec1};
+    if (multi && rec1.fail != 0) nn = load_rec2(t, rec1.fail);
 
     // ---- base candidates -------------------------------------------------------------------------
     float g[4];
@@ -173,11 +189,21 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
           eval(early[q], 64 * q + lane < r.count, r.begin + max(0, min(64 * q + lane, r.count - 1)) + 1, p, 0);
       }
       for (int level = 0;; ++level) {
+        int first = 0;  // arcs of this level already requested at the start of the frame
+        if (level == 0) first = 64 * kEarly;
+        if (level == 1) {
+          first = 64 * kEarly1;
+#pragma unroll
+          for (int q = 0; q < kEarly1; ++q) {
+            if (q == 0 || 64 * q < r.count)
+              eval(early1[q], 64 * q + lane < r.count, r.begin + max(0, min(64 * q + lane, r.count - 1)) + 1, p, 1);
+          }
+        }
         // Further arcs, up to four batches at a time so that their latencies overlap.  Every lane loads (the
         // index is clamped into the row) so that the load and its use stay in one block; lanes past the
         // end of the row are discarded by `valid`.
-        constexpr int kGroup = kEarly > 1 ? 4 : 1;
-        for (int j0 = (level == 0 ? 64 * kEarly : 0); j0 < r.count; j0 += 64 * kGroup) {
+        constexpr int kGroup = GROUP;
+        for (int j0 = first; j0 < r.count; j0 += 64 * kGroup) {
           ArcRec more[kGroup];
 #pragma unroll
           for (int q = 0; q < kGroup; ++q) more[q] = t.arc[r.begin + min(j0 + 64 * q + lane, r.count - 1)];
@@ -189,8 +215,15 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
         }
         p = __fadd_rn(p, r.backoff);
         if (r.fail == 0) break;
-        r = nrec;
-        if (r.fail != 0) nrec = load_rec(t, r.fail);
+        // one load serves two chain states: the cursor the first two, `nn` the next two, and so on
+        if (level == 0) {
+          r = rec1;
+        } else if ((level & 1) != 0) {
+          r = nn.a;
+        } else {
+          r = nn.b;
+          if (r.fail != 0) nn = load_rec2(t, r.fail);
+        }
       }
     }
 
@@ -284,6 +317,10 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
   cur.rec.count = uniform_i(cur.rec.count);
   cur.rec.fail = uniform_i(cur.rec.fail);
   cur.rec.backoff = uniform_f(cur.rec.backoff);
+  cur.rec1.begin = uniform_i(cur.rec1.begin);
+  cur.rec1.count = uniform_i(cur.rec1.count);
+  cur.rec1.fail = uniform_i(cur.rec1.fail);
+  cur.rec1.backoff = uniform_f(cur.rec1.backoff);
   cur.p_root = uniform_f(cur.p_root);
   cur.eos_boost = uniform_f(cur.eos_boost);
   out_val = uniform_f(out_val);
@@ -349,22 +386,30 @@ __device__ __forceinline__ void guess_boundary_1k(const TreeView& t, float (&x)[
 //   EDGE (pass 1 of the multi-frame decoder): the range starts from a guess when it does not begin the call
 //   (f0 > 0) and marks its last state word when its own guess for the next range (f1 < T) turns out right.
 template <bool COMPARE, bool FULL, int SEL, bool EDGE>
-__device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
+__device__ __forceinline__ bool run_frames_1k(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
                                               int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s_in,
                                               int last_in, int T, const int32_t* __restrict__ states0,
                                               int32_t* __restrict__ tokens, int32_t* __restrict__ states,
                                               float* __restrict__ scores, float* row, unsigned* tags, int lane) {
-  if (f0 >= f1) return;
+  if (f0 >= f1) return true;
   constexpr bool GUESS = EDGE && !COMPARE;
   const int V = t.V;
   const float* rp = logp + static_cast<size_t>(b) * row_stride + static_cast<size_t>(f0) * frame_stride;
-  constexpr int NB = 3;  // ring size
+#ifndef PB_RING_FUSED
+#define PB_RING_FUSED 3
+#endif
+  constexpr int NB = (COMPARE || SEL != 0) ? 3 : PB_RING_FUSED;  // ring size
   // Batches of 64 arcs requested at the start of a frame: 256 arcs cover all but a few states; the two-stage
   // rules hold more state in registers and take half of that, a re-run (16 waves per workgroup) one batch.
   constexpr int kEarlyBatches = COMPARE ? 1 : (SEL == 0 ? 4 : 2);
+  // ... of the second chain state, and batches per round of what remains of a long arc row (a re-run has the
+  // registers for eight: its frames are mostly deep states, whose chains end in such rows)
+  constexpr int kEarlyBatches1 = COMPARE ? 4 : (SEL == 0 ? 4 : (SEL == 1 ? 2 : 0));
+  constexpr int kArcGroup = COMPARE ? 8 : 4;
   float xb[NB][16], c[16];
   load16<FULL>(rp, 0, V, lane, -INFINITY, xb[0]);
   if (f0 + 1 < f1) load16<FULL>(rp + frame_stride, 0, V, lane, -INFINITY, xb[1]);
+  if (NB > 3 && f0 + 2 < f1) load16<FULL>(rp + 2 * frame_stride, 0, V, lane, -INFINITY, xb[2]);
   load16<FULL>(t.root_score, 0, V, lane, 0.0f, c);  // needs no state: requested before the state is looked at
   StoredLane<SEL == 2> stored;
   if (COMPARE) stored.fetch(lane, f0, f1, B, b, tokens, states);
@@ -382,7 +427,7 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
   }
   if (!valid_state(t, s)) {
     fill_invalid(B, b, f0, f1, tokens, states, scores, lane);
-    return;
+    return false;
   }
   Cursor cur = cursor_at(t, s);
   float c_p = cur.p_root;
@@ -406,7 +451,7 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
     const bool more = f + NB - 1 < f1;
     float val;
     int tok;
-    frame_1k<FULL, SEL, kEarlyBatches>(t, cur, xb[U], c, c_p, alpha, row, tags, lane, last, f + 1 < f1,
+    frame_1k<FULL, SEL, kEarlyBatches, kEarlyBatches1, kArcGroup>(t, cur, xb[U], c, c_p, alpha, row, tags, lane, last, f + 1 < f1,
                         [&]() {
                           if (STEADY || more) load16<FULL>(rpn, 0, V, lane, -INFINITY, xb[(U + NB - 1) % NB]);
                         },
@@ -426,6 +471,8 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
         // met the stored trajectory: this frame is written too (its score may differ), the rest stands
         if (stored.state_at(slot) == word && (SEL != 2 || stored.token_at(slot) == tok)) {
           out.template flush<true>(lane, slot + 1, B, b, tokens, states, scores);
+          PB_STAT(0, 1);
+          PB_STAT(1, f - f0 + 1);
           return true;
         }
       }
@@ -442,12 +489,18 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
   using std::integral_constant;
   int fb = f0;
   for (; fb + NB <= f1; fb += NB) {  // whole turns of the ring: straight-line code
-    if (do_frame(integral_constant<int, 0>{}, integral_constant<bool, true>{}, fb)) return;
-    if (do_frame(integral_constant<int, 1>{}, integral_constant<bool, true>{}, fb + 1)) return;
-    if (do_frame(integral_constant<int, 2>{}, integral_constant<bool, true>{}, fb + 2)) return;
+    if (do_frame(integral_constant<int, 0>{}, integral_constant<bool, true>{}, fb)) return true;
+    if (do_frame(integral_constant<int, 1>{}, integral_constant<bool, true>{}, fb + 1)) return true;
+    if (do_frame(integral_constant<int, 2>{}, integral_constant<bool, true>{}, fb + 2)) return true;
+    if constexpr (NB > 3) {
+      if (do_frame(integral_constant<int, 3>{}, integral_constant<bool, true>{}, fb + 3)) return true;
+    }
   }
-  if (fb < f1 && do_frame(integral_constant<int, 0>{}, integral_constant<bool, false>{}, fb)) return;
-  if (fb + 1 < f1 && do_frame(integral_constant<int, 1>{}, integral_constant<bool, false>{}, fb + 1)) return;
+  if (fb < f1 && do_frame(integral_constant<int, 0>{}, integral_constant<bool, false>{}, fb)) return true;
+  if (fb + 1 < f1 && do_frame(integral_constant<int, 1>{}, integral_constant<bool, false>{}, fb + 1)) return true;
+  if constexpr (NB > 3) {
+    if (fb + 2 < f1 && do_frame(integral_constant<int, 2>{}, integral_constant<bool, false>{}, fb + 2)) return true;
+  }
   if (guessable && f1 < T) {
     // The guess the next range starts from, made here from the same rows; if it is what this range really
     // ends in, the last state word says so.
@@ -473,6 +526,12 @@ __device__ __forceinline__ void run_frames_1k(const TreeView& t, const float* __
     }
   }
   if (DEFER) out.template flush<COMPARE>(lane, f1 - out.base, B, b, tokens, states, scores);
+  if (COMPARE) {
+    PB_STAT(0, 1);
+    PB_STAT(1, f1 - f0);
+    PB_STAT(2, 1);
+  }
+  return false;  // (a re-run: the end of the range was reached without meeting the stored trajectory)
 }
 
 // LDS of one wave: a copy of the current row and the token marks.
@@ -519,6 +578,9 @@ __global__ void __launch_bounds__(512) frames_fix_kernel(DeviceTree dt, TreePick
   extern __shared__ float lds[];
   __shared__ int assumed[64], assumed_tok[64];
   __shared__ unsigned bad_words[2];
+#ifdef PB_STATS
+  const long long kernel_c0 = wall_clock64();
+#endif
   const int lane = threadIdx.x & 63, wave = uniform_i(threadIdx.x >> 6), nwaves = blockDim.x >> 6;
   const int b = blockIdx.x;
   float* row = lds + wave * kWaveLdsFloats;
@@ -531,9 +593,21 @@ __global__ void __launch_bounds__(512) frames_fix_kernel(DeviceTree dt, TreePick
   fix_segments<SEL == 2>(T, B, b, seg_len, nseg, tokens, states, assumed, assumed_tok, bad_words, lane, wave, nwaves,
                          [&](int seg, int s, int last) {
                            const int f0 = seg * seg_len, f1 = min(T, f0 + seg_len);
-                           run_frames_1k<true, FULL, SEL, false>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s,
+#ifdef PB_STATS
+                           const long long c0 = wall_clock64();
+#endif
+                           const bool met = run_frames_1k<true, FULL, SEL, false>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s,
                                                                  last, T, nullptr, tokens, states, scores, row, tags, lane);
+#ifdef PB_STATS
+                           const long long dt = wall_clock64() - c0;
+                           PB_STAT(3, dt);
+                           if (lane == 0) atomicMax(&g_stats[4], static_cast<unsigned long long>(dt));
+#endif
+                           return met;
                          });
+#ifdef PB_STATS
+  if (lane == 0) atomicMax(&g_stats[5], static_cast<unsigned long long>(wall_clock64() - kernel_c0));
+#endif
 }
 
 // Single step: one wave per hypothesis, no speculation.  With a table of trees every hypothesis names its own.
@@ -789,6 +863,17 @@ int launch_frames_wave(const DeviceTree& t, const TreePick& pick, const float* d
   }
   return PB_OK;
 }
+
+#ifdef PB_STATS
+extern "C" int pb_debug_stats(unsigned long long* out8, int reset) {
+  if (hipMemcpyFromSymbol(out8, HIP_SYMBOL(g_stats), 8 * sizeof(unsigned long long)) != hipSuccess) return -1;
+  if (reset) {
+    unsigned long long z[8] = {0};
+    if (hipMemcpyToSymbol(HIP_SYMBOL(g_stats), z, sizeof(z)) != hipSuccess) return -1;
+  }
+  return 0;
+}
+#endif
 
 int g_beam_wave_max_k = 7;  // widest beam the wave kernel's LDS allows on the device, set once
 

@@ -7,12 +7,18 @@
 
 namespace pb {
 
-// One 16-byte record per state: everything a failure-chain hop needs in a single load.
-struct alignas(16) StateRec {
+// One 32-byte record per state: everything a failure-chain hop needs, for the state and for the state its
+// failure link leads to, so that one load serves two levels of the chain (kernels that walk level by level
+// read the first half).
+struct alignas(32) StateRec {
   int32_t arc_begin;  // first arc of the state in the (from_state, token)-sorted arc table
   int32_t arc_count;  // arcs leaving the state
   int32_t fail;       // failure link
   float backoff;      // backoff score paid when the state is abandoned
+  int32_t f_arc_begin;  // the same four fields of state `fail`
+  int32_t f_arc_count;
+  int32_t f_fail;
+  float f_backoff;
 };
 
 // One 8-byte record per arc; the arc with index j leads to state j + 1.

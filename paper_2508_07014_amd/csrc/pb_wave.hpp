@@ -23,7 +23,7 @@ using u64 = unsigned long long;
 // Scalar-load views: the tree is never written while kernels run, so wave-uniform reads may go
 // through the constant address space (scalar cache).
 struct TreeView {
-  const v4i PB_AS4* state;     // StateRec as four dwords: arc_begin, arc_count, fail, backoff bits
+  const v8i PB_AS4* state;     // StateRec as eight dwords: arc_begin, arc_count, fail, backoff bits, twice
   const float PB_AS4* p_root;
   const int32_t PB_AS4* root_next;
   const v8i PB_AS4* root_rec;  // RootRec as eight dwords
@@ -35,7 +35,7 @@ struct TreeView {
 
 __device__ __forceinline__ TreeView make_view(const DeviceTree& t) {
   TreeView v;
-  v.state = (const v4i PB_AS4*)t.state;
+  v.state = (const v8i PB_AS4*)t.state;
   v.p_root = (const float PB_AS4*)t.p_root;
   v.root_next = (const int32_t PB_AS4*)t.root_next;
   v.root_rec = (const v8i PB_AS4*)t.root_rec;
@@ -104,12 +104,15 @@ __device__ __forceinline__ bool valid_state(const TreeView& t, int s) {
   return static_cast<unsigned>(s) < static_cast<unsigned>(t.num_states);
 }
 
-struct Rec {  // wave-uniform copy of a StateRec
+struct Rec {  // wave-uniform copy of one half of a StateRec
   int begin, count, fail;
   float backoff;
 };
+struct Rec2 {  // a state and the state its failure link leads to
+  Rec a, b;
+};
 __device__ __forceinline__ Rec load_rec(const TreeView& t, int s) {
-  const v4i r = t.state[s];
+  const v4i r = reinterpret_cast<const v4i PB_AS4*>(t.state)[2 * s];
   Rec o;
   o.begin = r.x;
   o.count = r.y;
@@ -117,17 +120,33 @@ __device__ __forceinline__ Rec load_rec(const TreeView& t, int s) {
   o.backoff = __int_as_float(r.w);
   return o;
 }
+__device__ __forceinline__ Rec2 load_rec2(const TreeView& t, int s) {
+  const v8i r = t.state[s];
+  Rec2 o;
+  o.a.begin = r.s0;
+  o.a.count = r.s1;
+  o.a.fail = r.s2;
+  o.a.backoff = __int_as_float(r.s3);
+  o.b.begin = r.s4;
+  o.b.count = r.s5;
+  o.b.fail = r.s6;
+  o.b.backoff = __int_as_float(r.s7);
+  return o;
+}
 
 struct Cursor {  // wave-uniform decoding state of one hypothesis
   int s;
-  Rec rec;
+  Rec rec;   // of the state
+  Rec rec1;  // of the state its failure link leads to (meaningful when rec.fail != 0)
   float p_root;
   float eos_boost;  // boost of the EOS token in this state (Sec. II-C); 0 without an EOS rule
 };
 __device__ __forceinline__ Cursor cursor_at(const TreeView& t, int s) {
   Cursor c;
   c.s = s;
-  c.rec = load_rec(t, s);
+  const Rec2 r = load_rec2(t, s);
+  c.rec = r.a;
+  c.rec1 = r.b;
   c.p_root = t.p_root[s];
   c.eos_boost = 0.0f;
   if (t.eos >= 0) c.eos_boost = t.eos_score[s];
@@ -140,6 +159,7 @@ __device__ __forceinline__ Cursor cursor_from_root_rec(const v8i& r) {
   c.rec.count = r.s2;
   c.rec.fail = r.s3;
   c.rec.backoff = __int_as_float(r.s4);
+  c.rec1 = Rec{0, 0, 0, 0.0f};  // the root row leads to the root or a depth-1 state: the chain ends there
   c.p_root = __int_as_float(r.s5);
   c.eos_boost = __int_as_float(r.s6);
   return c;
@@ -250,13 +270,15 @@ constexpr int kLookBack = 8;
 // State word of a stored frame without the boundary bit (an invalid frame holds -1 and stays as it is).
 __device__ __forceinline__ int plain_state(int word) { return word < 0 ? word : (word & ~kGuessOk); }
 
-// Outputs that other waves of the same launch may read while or after they are written (pass 2) go
-// through relaxed agent-scope atomics on both sides; the fences around the workgroup barriers order them.
+// Outputs that other waves may read while or after they are written (pass 2) go through relaxed atomics on
+// both sides.  Only waves of one workgroup ever exchange such words -- a hypothesis is repaired by one
+// workgroup -- so stores, loads and the fences around the workgroup barriers all use workgroup scope (a wider
+// scope would write back and invalidate the L2 of the whole XCD at every barrier, tree included).
 __device__ __forceinline__ int peek_i32(const int32_t* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 __device__ __forceinline__ void publish_i32(int32_t* p, int v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
 __device__ __forceinline__ void fill_invalid(int B, int b, int f0, int f1, int32_t* tokens, int32_t* states,
@@ -319,52 +341,68 @@ struct StoredLane {
 };
 
 // Pass 2 for one hypothesis (one workgroup; its waves share the segments 1 .. nseg-1).
-//   rerun(seg, state, label): decodes segment `seg` again from that outcome until it meets what is stored.
+//   rerun(seg, state, label): decodes segment `seg` again from that outcome until it meets what is stored;
+//   returns false when it reached the end of the segment without meeting it (the outcome there may have changed).
 //   (a) every segment whose left neighbour has not certified its guess is re-run from the outcome pass 1 stored
-//       at the end of that neighbour.  Neighbours are re-run at the same time, so that outcome may be
-//       replaced meanwhile: (b) repairs it.
-//   (b) rounds: wave 0 compares the outcome at the end of every segment j-1 with what segment j was last
-//       decoded from and publishes the set of stale segments; the waves re-run those in parallel.  Segment 0
-//       is exact, so after round r the segments up to r + 1 are final: at most nseg rounds, in practice one
-//       or two.
-//   Words that cross waves are relaxed agent-scope atomics; a release fence before and an acquire fence
+//       at the end of that neighbour (read once, before any re-run starts).  A neighbour's re-run may replace
+//       that outcome: (b) repairs it.
+//   (b) rounds, entered only while some re-run has reached the end of its segment (nothing else can change an
+//       outcome at a boundary): wave 0 compares the outcome at the end of every segment j-1 with what segment
+//       j was last decoded from and publishes the set of stale segments; the waves re-run those in parallel.
+//       Segment 0 is exact, so after round r the segments up to r + 1 are final: at most nseg rounds, in
+//       practice none.
+//   Words that cross waves are relaxed workgroup-scope atomics; a release fence before and an acquire fence
 //   after each workgroup barrier order them.
 template <bool WITH_TOKENS, typename Rerun>
 __device__ __forceinline__ void fix_segments(int T, int B, int b, int seg_len, int nseg, int32_t* tokens,
                                              int32_t* states, int* assumed, int* assumed_tok, unsigned* bad_words,
                                              int lane, int wave, int nwaves, Rerun&& rerun) {
+  auto end_word_ptr = [&](int seg) { return states + static_cast<size_t>((seg + 1) * seg_len - 1) * B + b; };
   auto end_word_of = [&](int seg) {  // state word of the last frame of segment `seg` (boundary bit included)
-    return peek_i32(states + static_cast<size_t>((seg + 1) * seg_len - 1) * B + b);
+    return peek_i32(end_word_ptr(seg));
   };
   auto end_token_of = [&](int seg) {  // label of the last frame of segment `seg`
     if (!WITH_TOKENS) return -1;
     return peek_i32(tokens + static_cast<size_t>((seg + 1) * seg_len - 1) * B + b);
   };
-  {
-    // every wave reads the outcome before every segment in one access (lane j: the end of segment j - 1) and
-    // records, for its own segments, exactly the value it decides with
-    const bool has = lane >= 1 && lane < nseg;
-    const int words = has ? end_word_of(lane - 1) : -1;
+  // Wave 0 reads the outcome before every segment in one access (lane j: the end of segment j - 1), records
+  // it as what segment j is decided from, and publishes the set of segments whose guess is not certified; the
+  // k-th of them goes to wave k mod nwaves, so that the re-runs spread evenly over the waves.
+  const bool has = lane >= 1 && lane < nseg;
+  int words = -1;
+  if (wave == 0) {
+    words = has ? end_word_of(lane - 1) : -1;
     const int labels = has ? end_token_of(lane - 1) : -1;
-    for (int seg = 1 + wave; seg < nseg; seg += nwaves) {
-      const int word = __builtin_amdgcn_readlane(words, seg), last = __builtin_amdgcn_readlane(labels, seg);
-      const int s = plain_state(word);
-      if (lane == 0) {
-        assumed[seg] = s;
-        assumed_tok[seg] = last;
-      }
-      if (word < 0 || (word & kGuessOk) == 0) rerun(seg, s, last);
+    if (has) {
+      assumed[lane] = plain_state(words);
+      assumed_tok[lane] = labels;
+    }
+    const u64 todo = __ballot(has && (words < 0 || (words & kGuessOk) == 0));
+    if (lane == 0) {
+      bad_words[0] = static_cast<unsigned>(todo);
+      bad_words[1] = static_cast<unsigned>(todo >> 32);
+    }
+  }
+  __syncthreads();
+  bool dirty = false;
+  {
+    u64 todo = (static_cast<u64>(bad_words[1]) << 32) | bad_words[0];
+    for (int k = 0; todo != 0; ++k) {
+      const int seg = first_lane(todo);
+      todo &= todo - 1;
+      if (k % nwaves == wave) dirty = !rerun(seg, assumed[seg], assumed_tok[seg]) || dirty;
     }
   }
   for (;;) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-    __syncthreads();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    const bool any = __syncthreads_or(dirty) != 0;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    if (!any) break;
+    dirty = false;
     if (wave == 0) {
-      const bool check = lane >= 1 && lane < nseg;
-      const int have = check ? plain_state(end_word_of(lane - 1)) : 0;
-      const int have_tok = check ? end_token_of(lane - 1) : 0;
-      const bool stale = check && (have != assumed[lane] || (WITH_TOKENS && have_tok != assumed_tok[lane]));
+      const int have = has ? plain_state(end_word_of(lane - 1)) : 0;
+      const int have_tok = has ? end_token_of(lane - 1) : 0;
+      const bool stale = has && (have != assumed[lane] || (WITH_TOKENS && have_tok != assumed_tok[lane]));
       if (stale) {
         assumed[lane] = have;
         assumed_tok[lane] = have_tok;
@@ -377,18 +415,19 @@ __device__ __forceinline__ void fix_segments(int T, int B, int b, int seg_len, i
     }
     __syncthreads();
     u64 bad = (static_cast<u64>(bad_words[1]) << 32) | bad_words[0];
-    if (bad == 0) break;
     for (int k = 0; bad != 0; ++k) {  // the k-th stale segment goes to wave k mod nwaves
       const int seg = first_lane(bad);
       bad &= bad - 1;
-      if (k % nwaves == wave) rerun(seg, assumed[seg], assumed_tok[seg]);
+      if (k % nwaves == wave) dirty = !rerun(seg, assumed[seg], assumed_tok[seg]) || dirty;
     }
   }
-  // every re-run is done: the boundary bits of pass 1 leave the output
-  if (wave == 0 && lane < nseg - 1) {
-    int32_t* p = states + static_cast<size_t>((lane + 1) * seg_len - 1) * B + b;
-    const int word = peek_i32(p);
-    if (word >= 0 && (word & kGuessOk) != 0) publish_i32(p, word & ~kGuessOk);
+  // every re-run is done: the boundary bits of pass 1 leave the output.  A word that a re-run has replaced
+  // meanwhile carries no bit (or marks an invalid frame) and must stay as it is: compare-and-swap against the
+  // value read at the start.
+  if (wave == 0 && has && words >= 0 && (words & kGuessOk) != 0) {
+    int expected = words;
+    __hip_atomic_compare_exchange_strong(end_word_ptr(lane - 1), &expected, words & ~kGuessOk, __ATOMIC_RELAXED,
+                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
   }
 }
 

@@ -410,13 +410,13 @@ __device__ __forceinline__ void guess_boundary_wide(const TreeView& t, int v0, i
 //   rs: root scores of the row in LDS, zero-padded to nchp chunks; tags: this wave's token marks (32 * nchp words)
 //   nchp: chunks per row rounded up to a whole turn of the ring (chunks past the row load nothing)
 template <bool COMPARE, bool FULL, int SEL, bool EDGE>
-__device__ __forceinline__ void run_frames_wide(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
+__device__ __forceinline__ bool run_frames_wide(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
                                                 int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s_in,
                                                 int last_in, int T, const int32_t* __restrict__ states0,
                                                 int32_t* __restrict__ tokens, int32_t* __restrict__ states,
                                                 float* __restrict__ scores, const float* rs, unsigned* tags, int nchp,
                                                 int lane) {
-  if (f0 >= f1) return;
+  if (f0 >= f1) return true;
   constexpr bool GUESS = EDGE && !COMPARE;
   const int V = t.V;
   const int nch = (V + kChunk - 1) / kChunk;
@@ -442,7 +442,7 @@ __device__ __forceinline__ void run_frames_wide(const TreeView& t, const float* 
   }
   if (!valid_state(t, s)) {
     fill_invalid(B, b, f0, f1, tokens, states, scores, lane);
-    return;
+    return false;
   }
   Cursor cur = cursor_at(t, s);
   LaneOut out{f0, 0, 0, 0.0f};
@@ -504,7 +504,7 @@ __device__ __forceinline__ void run_frames_wide(const TreeView& t, const float* 
       // met the stored trajectory: this frame is written too (its score may differ), the rest stands
       if (stored.state_at(slot) == word && (SEL != 2 || stored.token_at(slot) == o.tok)) {
         out.template flush<true>(lane, slot + 1, B, b, tokens, states, scores);
-        return;
+        return true;
       }
     }
     if (track) {
@@ -526,6 +526,7 @@ __device__ __forceinline__ void run_frames_wide(const TreeView& t, const float* 
     rp += frame_stride;
   }
   out.template flush<COMPARE>(lane, f1 - out.base, B, b, tokens, states, scores);
+  return false;  // (a re-run: the end of the range was reached without meeting the stored trajectory)
 }
 
 // Root scores of a row for the pass over it: zero beyond V, NaN in the blank and EOS columns (those two tokens
@@ -614,7 +615,7 @@ __global__ void __launch_bounds__(512) wide_fix_kernel(DeviceTree dt, TreePick p
   fix_segments<SEL == 2>(T, B, b, seg_len, nseg, tokens, states, assumed, assumed_tok, bad_words, lane, wave, nwaves,
                          [&](int seg, int s, int last) {
                            const int f0 = seg * seg_len, f1 = min(T, f0 + seg_len);
-                           run_frames_wide<true, FULL, SEL, false>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1,
+                           return run_frames_wide<true, FULL, SEL, false>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1,
                                                                    s, last, T, nullptr, tokens, states, scores, rs, tags,
                                                                    nchp, lane);
                          });
