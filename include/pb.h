@@ -204,6 +204,24 @@ int pb_fuse_frames_select(const pb_tree* tree, const float* d_logp, int64_t fram
                           int32_t mode, int32_t* d_tokens, int32_t* d_states, float* d_scores, void* hip_stream);
 
 /*
+ * pb_fuse_frames_ws -- pb_fuse_frames_select with a caller-owned workspace, the faster form of the same call
+ * (identical outputs).  The decoder cuts the T frames of every hypothesis into segments decoded side by side,
+ * each from a guess of the state the frame before it ends in; with the workspace a segment that finds the
+ * guess for its right neighbour wrong repairs the neighbour's first frames itself and leaves them there, and
+ * nothing is decoded a second time.
+ *   d_workspace: device memory of at least pb_fuse_frames_workspace_bytes(tree, T, B) bytes, 4-byte aligned,
+ *   used only during the call (contents before and after mean nothing; two calls that overlap in time need
+ *   two workspaces).  pb_fuse_frames_workspace_bytes returns the size (0 when the call needs none: T or B zero,
+ *   or rows wider than 1024 tokens, which are repaired without it), or PB_EINVAL for a null tree or negative sizes.
+ *   PB_EINVAL also for a workspace that is null, too small or misaligned when one is needed.
+ */
+int64_t pb_fuse_frames_workspace_bytes(const pb_tree* tree, int32_t T, int32_t B);
+int pb_fuse_frames_ws(const pb_tree* tree, const float* d_logp, int64_t frame_stride, int64_t row_stride,
+                      const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B, int32_t mode,
+                      int32_t* d_tokens, int32_t* d_states, float* d_scores, void* d_workspace, int64_t workspace_bytes,
+                      void* hip_stream);
+
+/*
  * pb_fuse_step_beam -- one beam-search step: expansion scores, pruning and the state gather by
  * parent (Alg. 1 Stage 3: hyps_expansion_score, prune_expanded, S[t]).  Hypotheses u*K .. u*K+K-1
  * are the beams of utterance u.  For every candidate (k, v) of utterance u

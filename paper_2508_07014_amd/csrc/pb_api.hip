@@ -199,9 +199,14 @@ int pb_fuse_step(const pb_tree* tree, const float* d_logp, int64_t row_stride, c
                              d_states_out, d_scores, hip_stream);
 }
 
-int pb_fuse_frames_select(const pb_tree* tree, const float* d_logp, int64_t frame_stride, int64_t row_stride,
-                          const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B,
-                          int32_t mode, int32_t* d_tokens, int32_t* d_states, float* d_scores, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// pb_fuse_frames_select and pb_fuse_frames_ws: d_patches is the optional workspace (null: none).
+int fuse_frames_any(const pb_tree* tree, const float* d_logp, int64_t frame_stride, int64_t row_stride,
+                    const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B, int32_t mode,
+                    int32_t* d_tokens, int32_t* d_states, float* d_scores, int32_t* d_patches, void* hip_stream) {
   if (!on_device(tree) || B < 0 || T < 0) return PB_EINVAL;
   if (mode != PB_SELECT_FUSED && mode != PB_SELECT_TWO_STAGE && mode != PB_SELECT_TWO_STAGE_CTC) return PB_EINVAL;
   if (B == 0 || T == 0) return PB_OK;
@@ -211,9 +216,40 @@ int pb_fuse_frames_select(const pb_tree* tree, const float* d_logp, int64_t fram
   // (the segment decoder keeps a flag in bit 30 of the state words it stores: larger trees take the plain kernel)
   if (pb::wave_path_ok(tree->dev, d_logp, frame_stride, row_stride) && tree->dev.num_states < (1 << 30))
     return pb::launch_frames_wave(tree->dev, pb::TreePick{}, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, mode,
-                                  d_tokens, d_states, d_scores, stream);
+                                  d_tokens, d_states, d_scores, d_patches, stream);
   return pb::launch_fuse(tree->dev, pb::TreePick{}, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, mode, d_tokens,
                          d_states, d_scores, stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+int pb_fuse_frames_select(const pb_tree* tree, const float* d_logp, int64_t frame_stride, int64_t row_stride,
+                          const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B,
+                          int32_t mode, int32_t* d_tokens, int32_t* d_states, float* d_scores, void* hip_stream) {
+  return fuse_frames_any(tree, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, mode, d_tokens, d_states,
+                         d_scores, nullptr, hip_stream);
+}
+
+int64_t pb_fuse_frames_workspace_bytes(const pb_tree* tree, int32_t T, int32_t B) {
+  if (!tree || T < 0 || B < 0) return PB_EINVAL;
+  if (T == 0 || B == 0) return 0;
+  pb::DeviceTree shape;  // (a host-only tree has no device record: the size depends on the vocabulary alone)
+  shape.vocab_size = tree->host.vocab_size;
+  return pb::frames_workspace_bytes(shape, T, B);
+}
+
+int pb_fuse_frames_ws(const pb_tree* tree, const float* d_logp, int64_t frame_stride, int64_t row_stride,
+                      const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B, int32_t mode,
+                      int32_t* d_tokens, int32_t* d_states, float* d_scores, void* d_workspace, int64_t workspace_bytes,
+                      void* hip_stream) {
+  if (!on_device(tree) || B < 0 || T < 0 || workspace_bytes < 0) return PB_EINVAL;
+  const int64_t need = (T == 0 || B == 0) ? 0 : pb::frames_workspace_bytes(tree->dev, T, B);
+  if (need > 0 && (!d_workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(d_workspace) & 3u) != 0))
+    return PB_EINVAL;
+  return fuse_frames_any(tree, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, mode, d_tokens, d_states,
+                         d_scores, need > 0 ? static_cast<int32_t*>(d_workspace) : nullptr, hip_stream);
 }
 
 int pb_fuse_frames(const pb_tree* tree, const float* d_logp, int64_t frame_stride, int64_t row_stride,
@@ -340,7 +376,7 @@ int pb_fuse_frames_forest(const pb_forest* forest, const float* d_logp, int64_t 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (pb::wave_path_ok(forest->proto, d_logp, frame_stride, row_stride) && forest->proto.num_states < (1 << 30))
     return pb::launch_frames_wave(forest->proto, pick, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B,
-                                  mode, d_tokens, d_states, d_scores, stream);
+                                  mode, d_tokens, d_states, d_scores, nullptr, stream);
   return pb::launch_fuse(forest->proto, pick, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, mode,
                          d_tokens, d_states, d_scores, stream);
 }

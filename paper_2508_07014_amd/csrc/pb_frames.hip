@@ -376,6 +376,53 @@ __device__ __forceinline__ void guess_boundary_1k(const TreeView& t, float (&x)[
   }
 }
 
+// A wrong boundary guess, repaired where it is found.  Track A starts from the real outcome (state sA, label
+// lastA) at the end of a range, track B from the guess (sB, lastB) the next range was decoded from; both are
+// decoded over the frames that follow, at most n_max of them, until they agree on state and label -- from there
+// on what the next range wrote is right.  The frames of track A up to that point go to `patch` (entry i in lane
+// i) and their number is returned; 0 if the tracks have not met.   rp: row of the first frame after the range.
+template <bool FULL, int SEL>
+__device__ __forceinline__ int run_on_1k(const TreeView& t, const float* __restrict__ rp, int64_t frame_stride,
+                                         float alpha, int sA, int lastA, int sB, int lastB, int n_max,
+                                         int32_t* __restrict__ patch, float* row, unsigned* tags, int lane) {
+  if (n_max <= 0 || !valid_state(t, sB)) return 0;
+  const int V = t.V;
+  float x[16], xn[16], c[16];  // (one cache of base boosts for both tracks: it is rebuilt whenever p_root changes)
+  load16<FULL>(rp, 0, V, lane, -INFINITY, x);
+  Cursor ca = cursor_at(t, sA), cb = cursor_at(t, sB);
+  float c_p = ca.p_root;
+  rebuild_base_boost<FULL, SEL>(t, lane, c_p, alpha, c);
+  int e_tok = 0, e_st = 0;
+  float e_sc = 0.0f;
+  for (int i = 0; i < n_max; ++i) {
+    float valA, valB;
+    int tokA, tokB;
+    bool in_lds;
+    const float* rpn = rp + static_cast<int64_t>(min(i + 1, n_max - 1)) * frame_stride;  // (the last frame asks for its own row again)
+    frame_1k<FULL, SEL, 1, 1, 4>(t, ca, x, c, c_p, alpha, row, tags, lane, lastA, true,
+                                 [&]() { load16<FULL>(rpn, 0, V, lane, -INFINITY, xn); }, valA, tokA, in_lds);
+    frame_1k<FULL, SEL, 1, 1, 4>(t, cb, x, c, c_p, alpha, row, tags, lane, lastB, true, []() {}, valB, tokB, in_lds);
+    if (lane == i) {
+      e_tok = tokA;
+      e_st = ca.s;
+      e_sc = valA;
+    }
+    lastA = tokA;
+    lastB = tokB;
+    if (ca.s == cb.s && (SEL != 2 || tokA == tokB)) {
+      if (lane <= i) {
+        patch[4 + lane] = e_tok;
+        patch[4 + kPatchMax + lane] = e_st;
+        patch[4 + 2 * kPatchMax + lane] = __float_as_int(e_sc);
+      }
+      return i + 1;
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j) x[j] = xn[j];
+  }
+  return 0;
+}
+
 // Decodes frames [f0, f1) of hypothesis b (V <= 1024) starting in state s_in with previous label
 // last_in (values that may still be in flight from a load: they are first looked at after the row
 // loads have been issued; an invalid state marks the frames).  With COMPARE set, stops after the
@@ -384,11 +431,14 @@ __device__ __forceinline__ void guess_boundary_1k(const TreeView& t, float (&x)[
 // then valid from there on).
 //   Rows travel through a ring of three register buffers: the frame in hand and the two after it.
 //   EDGE (pass 1 of the multi-frame decoder): the range starts from a guess when it does not begin the call
-//   (f0 > 0) and marks its last state word when its own guess for the next range (f1 < T) turns out right.
+//   (f0 > 0) and marks its last state word when its own guess for the next range (f1 < T) turns out right -- or,
+//   given a patch record (`patch`, with `next_len` the length of the next range), when it has repaired a wrong
+//   guess itself.
 template <bool COMPARE, bool FULL, int SEL, bool EDGE>
 __device__ __forceinline__ bool run_frames_1k(const TreeView& t, const float* __restrict__ logp, int64_t frame_stride,
                                               int64_t row_stride, float alpha, int B, int b, int f0, int f1, int s_in,
                                               int last_in, int T, const int32_t* __restrict__ states0,
+                                              int32_t* __restrict__ patch, int next_len,
                                               int32_t* __restrict__ tokens, int32_t* __restrict__ states,
                                               float* __restrict__ scores, float* row, unsigned* tags, int lane) {
   if (f0 >= f1) return true;
@@ -427,6 +477,7 @@ __device__ __forceinline__ bool run_frames_1k(const TreeView& t, const float* __
   }
   if (!valid_state(t, s)) {
     fill_invalid(B, b, f0, f1, tokens, states, scores, lane);
+    if (GUESS && patch != nullptr && lane == 0) patch[0] = 0;
     return false;
   }
   Cursor cur = cursor_at(t, s);
@@ -517,13 +568,26 @@ __device__ __forceinline__ bool run_frames_1k(const TreeView& t, const float* __
     rebuild_base_boost<FULL, SEL>(t, opaque(lane), 0.0f, alpha, c0);
     int g, glabel;
     guess_boundary_1k<FULL, SEL>(t, xl, rp - frame_stride, frame_stride, f1 - 1, states0, b, c0, lane, g, glabel);
-    if (g == cur.s && (SEL != 2 || glabel == last)) {
+    bool certified = g == cur.s && (SEL != 2 || glabel == last);
+    if (patch != nullptr) {
+      int npatch = 0;
+      if (!certified) {
+        // (at most up to the frame before the last one of the next range, whose state word carries that range's own bit)
+        npatch = run_on_1k<FULL, SEL>(t, rp, frame_stride, alpha, cur.s, last, g, glabel, min(kPatchMax, next_len - 1),
+                                      patch, row, tags, lane);
+        certified = npatch > 0;
+      }
+      if (lane == 0) patch[0] = npatch;
+    }
+    if (certified) {
       if (DEFER) {
         if (lane == f1 - 1 - out.base) out.st |= kGuessOk;
       } else if (lane == 0) {
         states[static_cast<size_t>(f1 - 1) * B + b] = cur.s | kGuessOk;
       }
     }
+  } else if (GUESS && patch != nullptr && f1 < T && lane == 0) {
+    patch[0] = 0;
   }
   if (DEFER) out.template flush<COMPARE>(lane, f1 - out.base, B, b, tokens, states, scores);
   if (COMPARE) {
@@ -545,7 +609,8 @@ __global__ void __launch_bounds__(256, 4) frames_spec_kernel(DeviceTree dt, Tree
                                                           int64_t frame_stride, int64_t row_stride,
                                                           const int32_t* __restrict__ states0,
                                                           const int32_t* __restrict__ last0, float alpha, int T, int B,
-                                                          int seg_len, int nseg, int32_t* __restrict__ tokens,
+                                                          int seg_len, int nseg, int32_t* __restrict__ patches,
+                                                          int32_t* __restrict__ tokens,
                                                           int32_t* __restrict__ states, float* __restrict__ scores) {
   extern __shared__ float lds[];
   const int lane = threadIdx.x & 63, wave = uniform_i(threadIdx.x >> 6);
@@ -565,15 +630,19 @@ __global__ void __launch_bounds__(256, 4) frames_spec_kernel(DeviceTree dt, Tree
     if (SEL == 2 && last0 != nullptr) last = last0[b];
   }
   if (!tree_ok) s = -1;  // an unknown tree marks every frame of the hypothesis like an invalid state
+  int32_t* patch = nullptr;  // the record of the boundary after this segment
+  if (patches != nullptr && f1 < T) patch = patches + (static_cast<size_t>(j) * B + b) * kPatchInts;
   run_frames_1k<false, FULL, SEL, true>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, T, states0,
-                                        tokens, states, scores, row, tags, lane);
+                                        patch, min(T, f1 + seg_len) - f1, tokens, states, scores, row, tags, lane);
 }
 
 // Pass 2: one workgroup per hypothesis; its waves share the segments j = 1 .. nseg-1.
 template <bool FULL, int SEL, bool FOREST>
 __global__ void __launch_bounds__(512) frames_fix_kernel(DeviceTree dt, TreePick pick, const float* __restrict__ logp,
                                                           int64_t frame_stride, int64_t row_stride, float alpha, int T,
-                                                          int B, int seg_len, int nseg, int32_t* __restrict__ tokens,
+                                                          int B, int seg_len, int nseg,
+                                                          const int32_t* __restrict__ patches,
+                                                          int32_t* __restrict__ tokens,
                                                           int32_t* __restrict__ states, float* __restrict__ scores) {
   extern __shared__ float lds[];
   __shared__ int assumed[64], assumed_tok[64];
@@ -590,14 +659,15 @@ __global__ void __launch_bounds__(512) frames_fix_kernel(DeviceTree dt, TreePick
     if (!pick_tree(pick, b, mine)) return;  // pass 1 has marked every frame of this hypothesis (the whole workgroup leaves)
   }
   const TreeView t = make_view(mine);
-  fix_segments<SEL == 2>(T, B, b, seg_len, nseg, tokens, states, assumed, assumed_tok, bad_words, lane, wave, nwaves,
+  fix_segments<SEL == 2>(T, B, b, seg_len, nseg, tokens, states, scores, patches, assumed, assumed_tok, bad_words, lane,
+                         wave, nwaves,
                          [&](int seg, int s, int last) {
                            const int f0 = seg * seg_len, f1 = min(T, f0 + seg_len);
 #ifdef PB_STATS
                            const long long c0 = wall_clock64();
 #endif
                            const bool met = run_frames_1k<true, FULL, SEL, false>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s,
-                                                                 last, T, nullptr, tokens, states, scores, row, tags, lane);
+                                                                 last, T, nullptr, nullptr, 0, tokens, states, scores, row, tags, lane);
 #ifdef PB_STATS
                            const long long dt = wall_clock64() - c0;
                            PB_STAT(3, dt);
@@ -629,7 +699,7 @@ __global__ void __launch_bounds__(256) step_wave_kernel(DeviceTree dt, TreePick 
   const int s = tree_ok ? states_in[b] : -1;  // an unknown tree marks the hypothesis like an invalid state
   int last = -1;
   if (SEL == 2 && last_in != nullptr) last = last_in[b];
-  run_frames_1k<false, FULL, SEL, false>(t, logp, 0, row_stride, alpha, B, b, 0, 1, s, last, 1, nullptr, tokens,
+  run_frames_1k<false, FULL, SEL, false>(t, logp, 0, row_stride, alpha, B, b, 0, 1, s, last, 1, nullptr, nullptr, 0, tokens,
                                          states_out, scores, row, tags, lane);
 }
 
@@ -811,10 +881,16 @@ int launch_step_wave(const DeviceTree& t, const TreePick& pick, const float* d_l
   return hipGetLastError() == hipSuccess ? PB_OK : PB_EHIP;
 }
 
+int64_t frames_workspace_bytes(const DeviceTree& t, int32_t T, int32_t B) {
+  if (t.vocab_size > kChunk) return 0;  // (wide rows repair wrong guesses in pass 2)
+  const SegPlan plan = plan_segments(T, B, kTargetChains);
+  return static_cast<int64_t>(plan.nseg - 1) * B * kPatchInts * static_cast<int64_t>(sizeof(int32_t));
+}
+
 int launch_frames_wave(const DeviceTree& t, const TreePick& pick, const float* d_logp, int64_t frame_stride,
                        int64_t row_stride,
                        const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B, int sel,
-                       int32_t* d_tokens, int32_t* d_states, float* d_scores, hipStream_t stream) {
+                       int32_t* d_tokens, int32_t* d_states, float* d_scores, int32_t* d_patches, hipStream_t stream) {
   if (t.vocab_size > kChunk)
     return launch_frames_wide(t, pick, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, sel, d_tokens,
                               d_states, d_scores, stream);
@@ -830,7 +906,7 @@ int launch_frames_wave(const DeviceTree& t, const TreePick& pick, const float* d
 #define PB_SPEC(FULL, SEL, FOREST)                                                                                   \
   hipLaunchKernelGGL((frames_spec_kernel<FULL, SEL, FOREST>), dim3(static_cast<unsigned>(blocks)), dim3(64 * waves), \
                      lds, stream, t, pick, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B,        \
-                     seg_len, nseg, d_tokens, d_states, d_scores)
+                     seg_len, nseg, d_patches, d_tokens, d_states, d_scores)
 #define PB_LAUNCH(FULL, SEL) PB_SPEC(FULL, SEL, false)
 #define PB_LAUNCH_F(FULL, SEL) PB_SPEC(FULL, SEL, true)
   if (forest) {
@@ -847,8 +923,8 @@ int launch_frames_wave(const DeviceTree& t, const TreePick& pick, const float* d
     const size_t lds2 = static_cast<size_t>(fw) * kWaveLdsBytes;
 #define PB_FIX(FULL, SEL, FOREST)                                                                                     \
   hipLaunchKernelGGL((frames_fix_kernel<FULL, SEL, FOREST>), dim3(static_cast<unsigned>(B)), dim3(64 * fw), lds2,     \
-                     stream, t, pick, d_logp, frame_stride, row_stride, alpha, T, B, seg_len, nseg, d_tokens,         \
-                     d_states, d_scores)
+                     stream, t, pick, d_logp, frame_stride, row_stride, alpha, T, B, seg_len, nseg, d_patches,        \
+                     d_tokens, d_states, d_scores)
 #define PB_LAUNCH(FULL, SEL) PB_FIX(FULL, SEL, false)
 #define PB_LAUNCH_F(FULL, SEL) PB_FIX(FULL, SEL, true)
     if (forest) {

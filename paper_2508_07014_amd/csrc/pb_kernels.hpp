@@ -60,10 +60,13 @@ int launch_step_wave(const DeviceTree& t, const TreePick& pick, const float* d_l
                      const int32_t* d_states_in,
                      const int32_t* d_last, float alpha, int32_t B, int sel, int32_t* d_tokens, int32_t* d_states_out,
                      float* d_scores, hipStream_t stream);
+// d_patches: optional workspace of frames_workspace_bytes(t, T, B) bytes (null: wrong boundary guesses are
+// repaired by re-runs in pass 2 instead of patches from pass 1).
+int64_t frames_workspace_bytes(const DeviceTree& t, int32_t T, int32_t B);
 int launch_frames_wave(const DeviceTree& t, const TreePick& pick, const float* d_logp, int64_t frame_stride,
                        int64_t row_stride,
                        const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B, int sel,
-                       int32_t* d_tokens, int32_t* d_states, float* d_scores, hipStream_t stream);
+                       int32_t* d_tokens, int32_t* d_states, float* d_scores, int32_t* d_patches, hipStream_t stream);
 
 // Wave-per-beam kernel (pb_frames.hip): rows as for the wave path, V <= 1024 and a beam the LDS can hold.
 bool beam_wave_ok(const DeviceTree& t, const float* d_logp, int64_t row_stride, int32_t K);

@@ -267,6 +267,14 @@ constexpr int kGuessOk = 1 << 30;
 // says nothing about it, so the guess goes back to the last frame that moved it.
 constexpr int kLookBack = 8;
 
+// Patches (optional workspace of the multi-frame decoder).  A segment that finds its guess for the next segment
+// wrong decodes on from its real outcome, next to the trajectory the guess leads to, until the two meet -- at
+// most kPatchMax frames, usually one to three -- and leaves the frames it has decoded as a patch for the start
+// of the next segment.  The boundary then counts as certified, and pass 2 only copies the patch over what the
+// next segment wrote; nothing is decoded again.  One record per boundary: count, then tokens, states, scores.
+constexpr int kPatchMax = 16;
+constexpr int kPatchInts = 4 + 3 * kPatchMax;
+
 // State word of a stored frame without the boundary bit (an invalid frame holds -1 and stays as it is).
 __device__ __forceinline__ int plain_state(int word) { return word < 0 ? word : (word & ~kGuessOk); }
 
@@ -353,10 +361,32 @@ struct StoredLane {
 //       practice none.
 //   Words that cross waves are relaxed workgroup-scope atomics; a release fence before and an acquire fence
 //   after each workgroup barrier order them.
+//   patches: the workspace with one patch record per boundary, (j - 1) * B + b for the boundary before segment j
+//   (null: none); the patches are copied into the output first.
 template <bool WITH_TOKENS, typename Rerun>
 __device__ __forceinline__ void fix_segments(int T, int B, int b, int seg_len, int nseg, int32_t* tokens,
-                                             int32_t* states, int* assumed, int* assumed_tok, unsigned* bad_words,
-                                             int lane, int wave, int nwaves, Rerun&& rerun) {
+                                             int32_t* states, float* scores, const int32_t* __restrict__ patches,
+                                             int* assumed, int* assumed_tok, unsigned* bad_words, int lane, int wave,
+                                             int nwaves, Rerun&& rerun) {
+  if (patches != nullptr) {
+    // a quarter wave per boundary: lane q of the quarter copies entry q of the patch
+    const int sub = lane >> 4, q = lane & 15;
+    for (int j0 = 1 + 4 * wave; j0 < nseg; j0 += 4 * nwaves) {
+      const int j = j0 + sub;
+      if (j < nseg) {
+        const int32_t* rec = patches + (static_cast<size_t>(j - 1) * B + b) * kPatchInts;
+        const int count = rec[0];
+        const int tok = rec[4 + q], st = rec[4 + kPatchMax + q];
+        const float sc = __int_as_float(rec[4 + 2 * kPatchMax + q]);
+        if (q < count) {
+          const size_t o = static_cast<size_t>(j * seg_len + q) * B + b;
+          publish_i32(tokens + o, tok);
+          publish_i32(states + o, st);
+          scores[o] = sc;
+        }
+      }
+    }
+  }
   auto end_word_ptr = [&](int seg) { return states + static_cast<size_t>((seg + 1) * seg_len - 1) * B + b; };
   auto end_word_of = [&](int seg) {  // state word of the last frame of segment `seg` (boundary bit included)
     return peek_i32(end_word_ptr(seg));
@@ -383,7 +413,9 @@ __device__ __forceinline__ void fix_segments(int T, int B, int b, int seg_len, i
       bad_words[1] = static_cast<unsigned>(todo >> 32);
     }
   }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // (the patches, for the re-runs that compare with them)
   __syncthreads();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
   bool dirty = false;
   {
     u64 todo = (static_cast<u64>(bad_words[1]) << 32) | bad_words[0];

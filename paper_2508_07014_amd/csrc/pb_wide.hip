@@ -612,7 +612,8 @@ __global__ void __launch_bounds__(512) wide_fix_kernel(DeviceTree dt, TreePick p
   float* rs = lds;
   unsigned* tags = reinterpret_cast<unsigned*>(lds + nchp * kChunk) + wave * nchp * kTagWords;
   stage_root_scores(t, rs, nchp);
-  fix_segments<SEL == 2>(T, B, b, seg_len, nseg, tokens, states, assumed, assumed_tok, bad_words, lane, wave, nwaves,
+  fix_segments<SEL == 2>(T, B, b, seg_len, nseg, tokens, states, scores, nullptr, assumed, assumed_tok, bad_words, lane,
+                         wave, nwaves,
                          [&](int seg, int s, int last) {
                            const int f0 = seg * seg_len, f1 = min(T, f0 + seg_len);
                            return run_frames_wide<true, FULL, SEL, false>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1,

@@ -90,3 +90,17 @@ def gpu_beam_step(tree, d_logp, d_hyp, d_states, alpha, U, K, row_stride=None):
     pb.pb_fuse_step_beam(tree, d_logp, d_logp.shape[-1] if row_stride is None else row_stride, d_hyp, d_states, alpha,
                          U, K, d_tokens, d_parents, d_out, d_scores, stream_ptr())
     return d_tokens, d_parents, d_out, d_scores
+
+
+def frames_ws(tree, d_logp, d_states0, d_last0, alpha, mode, fill=-7):
+    """pb_fuse_frames_ws with a workspace of exactly the size the library asks for, filled with junk first."""
+    T, B, V = d_logp.shape
+    need = pb.pb_fuse_frames_workspace_bytes(tree, T, B)
+    ws = torch.full((max(need, 4) // 4,), 0x7f7f7f7f, dtype=torch.int32, device=DEV)
+    d_tokens = torch.full((T, B), fill, dtype=torch.int32, device=DEV)
+    d_states = torch.full((T, B), fill, dtype=torch.int32, device=DEV)
+    d_scores = torch.zeros((T, B), dtype=torch.float32, device=DEV)
+    pb.pb_fuse_frames_ws(tree, d_logp, B * V, V, d_states0, d_last0, alpha, T, B, mode, d_tokens, d_states, d_scores, ws,
+                         need, stream_ptr())
+    torch.cuda.synchronize()
+    return d_tokens.cpu().numpy(), d_states.cpu().numpy(), d_scores.cpu().numpy()

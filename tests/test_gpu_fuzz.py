@@ -15,7 +15,7 @@ if not torch.cuda.is_available():
     pytest.skip("no GPU", allow_module_level=True)
 
 import paper_2508_07014_amd as pb  # noqa: E402
-from gpu_helpers import DEV, dev  # noqa: E402
+from gpu_helpers import DEV, dev, frames_ws  # noqa: E402
 
 
 @pytest.mark.parametrize("chunk", range(6))
@@ -69,6 +69,9 @@ def test_frames_random_cases(chunk):
             assert np.allclose(sc[:, ok], want[2], atol=1e-5, rtol=0), where
             for b in bad:
                 assert np.all(tk[:, b] == -1) and np.all(st[:, b] == -1) and np.all(np.isnan(sc[:, b])), where
+            # the same call with a workspace (wrong boundary guesses repaired by patches): identical outputs
+            tk2, st2, sc2 = frames_ws(tr, d_logp, dev(s0), None if last0 is None else dev(last0), alpha, mode)
+            assert np.array_equal(tk2, tk) and np.array_equal(st2, st) and np.array_equal(sc2, sc, equal_nan=True), where
         pb.pb_free(tr)
 
 

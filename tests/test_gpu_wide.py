@@ -15,7 +15,7 @@ if not torch.cuda.is_available():
     pytest.skip("no GPU", allow_module_level=True)
 
 import paper_2508_07014_amd as pb  # noqa: E402
-from gpu_helpers import DEV, TOL, assert_scores, config_trees, dev, gpu_beam_step, gpu_score  # noqa: E402
+from gpu_helpers import DEV, TOL, assert_scores, config_trees, dev, frames_ws, gpu_beam_step, gpu_score  # noqa: E402
 
 
 def _random_tree(rng, V, blank, eos, nph, max_len, wmode, unk):
@@ -150,7 +150,31 @@ def test_frames_with_segments_of_64_frames_and_more(V, T, B):
         torch.cuda.synchronize()
         assert np.array_equal(d_tok.cpu().numpy(), want[0]) and np.array_equal(d_st.cpu().numpy(), want[1]), mode
         assert_scores(d_sc.cpu().numpy(), want[2])
+        got = frames_ws(tr, d_logp, dev(s0), None, 0.5, mode)
+        assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1]), mode
+        assert_scores(got[2], want[2])
     pb.pb_free(tr)
+
+
+def test_frames_with_workspace_config3_planted_and_blank_heavy():
+    """The workspace form at the headline shape on rows where many boundary guesses are wrong (planted phrases:
+    the hypotheses sit deep in the tree; blank-heavy rows: the state survives long stretches), every rule."""
+    cfg, toks, offs, ot, tr = config_trees(3)
+    B = cfg.batch
+    for kw in (dict(planting=W.Planting(toks, offs)), dict(blank_bias=8.0, blank_frac=0.75), {}):
+        logp = W.make_logp(cfg, steps=500, **kw)
+        d_logp = dev(logp)
+        for mode in (0, 1, 2):
+            want = ot.fuse_frames_select(logp, np.zeros(B, np.int32), None, cfg.alpha, mode)
+            got = frames_ws(tr, d_logp, dev(np.zeros(B, np.int32)), None, cfg.alpha, mode)
+            assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1]), (list(kw), mode)
+            assert np.array_equal(got[2], want[2]), (list(kw), mode)
+    need = pb.pb_fuse_frames_workspace_bytes(tr, 500, B)
+    assert need > 0
+    with pytest.raises(pb.PbError):      # a workspace that is too small is refused
+        ws = torch.zeros(need // 4, dtype=torch.int32, device=DEV)
+        pb.pb_fuse_frames_ws(tr, d_logp, B * cfg.vocab_size, cfg.vocab_size, dev(np.zeros(B, np.int32)), None, cfg.alpha,
+                             500, B, 0, ws, ws, ws, ws, need - 4, 0)
 
 
 def _chain_steps(tr, logp, alpha, mode=0):
