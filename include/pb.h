@@ -222,6 +222,21 @@ int pb_fuse_frames_ws(const pb_tree* tree, const float* d_logp, int64_t frame_st
                       void* hip_stream);
 
 /*
+ * pb_fuse_frames_static -- pb_fuse_frames_ws for callers that cannot allocate device memory (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation): the workspace is a fixed array inside
+ * the library, 1 MiB per GPU, held from the first pb_build on that GPU until the process ends.  The call
+ * allocates and frees nothing.  Outputs are those of pb_fuse_frames_ws.
+ *   PB_EUNSUPPORTED when pb_fuse_frames_workspace_bytes(tree, T, B) exceeds 1 MiB (208 bytes per segment
+ *   boundary; the library's segment plan keeps a call below 4096 boundaries = 832 KiB, so only a build with a
+ *   larger plan can exceed it).  Nothing in the array has to be cleared between calls (every call writes all it
+ *   reads), but every call on a GPU shares that GPU's array: two calls that overlap in time on one GPU, on any
+ *   streams, race and may both return wrong results.
+ */
+int pb_fuse_frames_static(const pb_tree* tree, const float* d_logp, int64_t frame_stride, int64_t row_stride,
+                          const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B,
+                          int32_t mode, int32_t* d_tokens, int32_t* d_states, float* d_scores, void* hip_stream);
+
+/*
  * pb_fuse_step_beam -- one beam-search step: expansion scores, pruning and the state gather by
  * parent (Alg. 1 Stage 3: hyps_expansion_score, prune_expanded, S[t]).  Hypotheses u*K .. u*K+K-1
  * are the beams of utterance u.  For every candidate (k, v) of utterance u

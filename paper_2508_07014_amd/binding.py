@@ -19,7 +19,7 @@ PB_SELECT_FUSED, PB_SELECT_TWO_STAGE, PB_SELECT_TWO_STAGE_CTC = 0, 1, 2
 
 EXPORTS = ["pb_build", "pb_free", "pb_info", "pb_host_arrays", "pb_state_prefix", "pb_score", "pb_fuse_step",
            "pb_fuse_frames", "pb_fuse_step_select", "pb_fuse_frames_select", "pb_fuse_frames_workspace_bytes",
-           "pb_fuse_frames_ws", "pb_fuse_step_beam", "pb_forest_build", "pb_forest_free", "pb_score_forest",
+           "pb_fuse_frames_ws", "pb_fuse_frames_static", "pb_fuse_step_beam", "pb_forest_build", "pb_forest_free", "pb_score_forest",
            "pb_fuse_step_forest", "pb_fuse_frames_forest", "pb_fuse_step_beam_forest", "pb_validate",
            "pb_validate_states", "pb_strerror"]
 
@@ -98,6 +98,9 @@ def load():
     lib.pb_fuse_frames_ws.restype = C.c_int
     lib.pb_fuse_frames_ws.argtypes = [vp, vp, C.c_int64, C.c_int64, vp, vp, C.c_float, C.c_int32, C.c_int32, C.c_int32,
                                       vp, vp, vp, vp, C.c_int64, vp]
+    lib.pb_fuse_frames_static.restype = C.c_int
+    lib.pb_fuse_frames_static.argtypes = [vp, vp, C.c_int64, C.c_int64, vp, vp, C.c_float, C.c_int32, C.c_int32,
+                                          C.c_int32, vp, vp, vp, vp]
     lib.pb_fuse_step_beam.restype = C.c_int
     lib.pb_fuse_step_beam.argtypes = [vp, vp, C.c_int64, vp, vp, C.c_float, C.c_int32, C.c_int32, vp, vp, vp, vp, vp]
     lib.pb_forest_build.restype = C.c_int
@@ -275,6 +278,13 @@ def pb_fuse_frames_ws(tree: Tree, d_logp, frame_stride: int, row_stride: int, d_
                                     _dptr(d_last0), alpha, T, B, mode, _dptr(d_tokens), _dptr(d_states),
                                     _dptr(d_scores), _dptr(d_workspace), workspace_bytes, stream or None),
            "pb_fuse_frames_ws")
+
+
+def pb_fuse_frames_static(tree: Tree, d_logp, frame_stride: int, row_stride: int, d_states0, d_last0, alpha: float,
+                          T: int, B: int, mode: int, d_tokens, d_states, d_scores, stream: int = 0):
+    _check(load().pb_fuse_frames_static(tree.handle, _dptr(d_logp), frame_stride, row_stride, _dptr(d_states0),
+                                        _dptr(d_last0), alpha, T, B, mode, _dptr(d_tokens), _dptr(d_states),
+                                        _dptr(d_scores), stream or None), "pb_fuse_frames_static")
 
 
 def pb_fuse_step_beam(tree: Tree, d_logp, row_stride: int, d_hyp_scores, d_states_in, alpha: float, U: int, K: int,

@@ -5,6 +5,7 @@
 #include <climits>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -15,6 +16,30 @@
 namespace {
 
 constexpr size_t kAlign = 256;
+
+// Scratch of pb_fuse_frames_static: the patch workspace of the multi-frame decoder as a fixed device array, for
+// callers that cannot allocate.  Every GPU the library runs on holds its own copy until the process ends.  In
+// host code the array's name is only a stand-in for the symbol: its device address is looked up once per device
+// (with that device current) and that address is what the launches get.
+constexpr int64_t kStaticScratchBytes = 1ll << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// With `device` current: the address of this device's copy of `scratch`.
+int lookup_scratch(int device) {
+  if (device < 0 || device >= kMaxDevices) return PB_OK;  // (such a device simply has no static scratch)
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[device] != nullptr) return PB_OK;
+  void* ptr = nullptr;
+  if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+    (void)hipGetLastError();
+    return PB_EHIP;
+  }
+  g_scratch_ptr[device] = ptr;
+  return PB_OK;
+}
 
 size_t padded(size_t bytes) { return (bytes + kAlign - 1) / kAlign * kAlign; }
 
@@ -60,6 +85,7 @@ int upload(pb_tree* tr, int device) {
     tr->dev.eos_score = n_es ? static_cast<const float*>(put(h.eos_score.data(), n_es)) : nullptr;
     tr->dev.eos_id = h.eos_id;
     if (rc == PB_OK) rc = pb::prepare_wave_kernels();
+    if (rc == PB_OK) rc = lookup_scratch(device);
     tr->dev.num_states = static_cast<int32_t>(h.state.size());
     tr->dev.vocab_size = h.vocab_size;
     tr->dev.blank_id = h.blank_id;
@@ -250,6 +276,18 @@ int pb_fuse_frames_ws(const pb_tree* tree, const float* d_logp, int64_t frame_st
     return PB_EINVAL;
   return fuse_frames_any(tree, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, mode, d_tokens, d_states,
                          d_scores, need > 0 ? static_cast<int32_t*>(d_workspace) : nullptr, hip_stream);
+}
+
+int pb_fuse_frames_static(const pb_tree* tree, const float* d_logp, int64_t frame_stride, int64_t row_stride,
+                          const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B,
+                          int32_t mode, int32_t* d_tokens, int32_t* d_states, float* d_scores, void* hip_stream) {
+  if (!on_device(tree) || B < 0 || T < 0) return PB_EINVAL;
+  const int64_t need = (T == 0 || B == 0) ? 0 : pb::frames_workspace_bytes(tree->dev, T, B);
+  if (need > kStaticScratchBytes) return PB_EUNSUPPORTED;  // more segment boundaries than the fixed array holds
+  void* ptr = (tree->device >= 0 && tree->device < kMaxDevices) ? g_scratch_ptr[tree->device] : nullptr;
+  if (need > 0 && ptr == nullptr) return PB_EHIP;
+  return fuse_frames_any(tree, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, mode, d_tokens, d_states,
+                         d_scores, need > 0 ? static_cast<int32_t*>(ptr) : nullptr, hip_stream);
 }
 
 int pb_fuse_frames(const pb_tree* tree, const float* d_logp, int64_t frame_stride, int64_t row_stride,
