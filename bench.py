@@ -77,6 +77,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-extra", action="store_true", help="skip the side measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing and the parity checks")
+    ap.add_argument("--config5-only", action="store_true",
+                    help="run only the config 5 greedy decode (V=8192, B=256, 200 steps) and print its block: the "
+                         "command behind the config 5 profile")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for hardware-counter runs)")
     args = ap.parse_args()
@@ -96,6 +99,21 @@ def main() -> int:
     dev = "cuda:0"
     torch.cuda.set_device(0)
     stream = int(torch.cuda.current_stream().cuda_stream)
+
+    if args.config5_only:
+        cfg5 = W.CONFIGS[5]
+        t5, o5 = W.make_phrases(cfg5)
+        tree5 = pb.pb_build(t5, o5, cfg5.vocab_size, cfg5.blank_id, device=0)
+        if args.calibrate_copy:
+            src = torch.ones(64 << 20, dtype=torch.float32, device=dev)
+            dst = torch.empty_like(src)
+            for _ in range(3):
+                dst.copy_(src)
+            torch.cuda.synchronize()
+            del src, dst
+        print(json.dumps({"config5_greedy": config5_greedy(torch, pb, W, dev, stream, tree5, t5, o5, not args.no_cpu,
+                                                           reps=args.steps)}))
+        return 0
 
     cfg = W.CONFIGS[3]
     T, B, V = cfg.steps, cfg.batch, cfg.vocab_size
@@ -198,6 +216,62 @@ def main() -> int:
                                          achieved, bytes_per_launch, (d_tok, d_st, d_sc, d_s0, d_ws, ws_bytes))
     print(json.dumps(out))
     return 0
+
+
+def config5_greedy(torch, pb, W, dev, stream, tree5, t5, o5, with_oracle, reps=5):
+    """Config 5 greedy decode (V = 8192, blank-free, B = 256, 200 steps), the per-step shape that moves 8 MiB:
+    the multi-frame call, one launch per step and HIP-graph replay of those launches."""
+    cfg5 = W.CONFIGS[5]
+    V5, T5, B5 = cfg5.vocab_size, cfg5.steps, cfg5.batch
+    logp5 = W.make_logp(cfg5)
+    d_lp5 = torch.from_numpy(logp5).to(dev)
+    z5 = torch.zeros(B5, dtype=torch.int32, device=dev)
+    o5b = [torch.empty((T5, B5), dtype=torch.int32, device=dev) for _ in range(2)] + \
+        [torch.empty((T5, B5), dtype=torch.float32, device=dev)]
+    bytes5 = T5 * B5 * (4 * V5 + 12) + 4 * B5
+
+    def rate5(ms):
+        return {"ms": ms, "us_per_frame": ms * 1e3 / T5, "hyp_frames_per_s": B5 * T5 / (ms * 1e-3),
+                "GBps": bytes5 / (ms * 1e-3) / 1e9, "frac_hbm": bytes5 / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+    c5 = {"workload": "config 5: greedy, 20000 phrases of 2-8 Zipf(1.1) tokens, V=8192, blank-free, alpha=0.5, "
+                      "B=256, 200 steps, N(0,3) log-softmax logits (1.6 GiB of log-probs, read once per decode)"}
+    fn = lambda: pb.pb_fuse_frames(tree5, d_lp5, B5 * V5, V5, z5, cfg5.alpha, T5, B5, o5b[0], o5b[1], o5b[2], stream)
+    fn()
+    c5["pb_fuse_frames"] = rate5(_events(torch, fn, reps))
+    w5 = None
+    if with_oracle:
+        from oracle import OracleTree
+        ot5 = OracleTree(t5, o5, V5, cfg5.blank_id)
+        w5 = ot5.fuse_frames(logp5, np.zeros(B5, np.int32), cfg5.alpha)
+        c5["pb_fuse_frames"]["parity"] = _same(o5b, w5)
+
+    def per_launch5(sp):
+        prev = z5
+        for t in range(T5):
+            pb.pb_fuse_step(tree5, d_lp5[t], V5, prev, cfg5.alpha, B5, o5b[0][t], o5b[1][t], o5b[2][t], sp)
+            prev = o5b[1][t]
+
+    o5b[0].fill_(-9)
+    per_launch5(stream)
+    torch.cuda.synchronize()
+    c5["per_launch"] = rate5(_events(torch, lambda: per_launch5(stream), 3))
+    if w5 is not None:
+        c5["per_launch"]["parity"] = _same(o5b, w5)
+    try:
+        g5 = torch.cuda.CUDAGraph()
+        side5 = torch.cuda.Stream()
+        side5.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side5):
+            with torch.cuda.graph(g5, stream=side5):
+                per_launch5(int(side5.cuda_stream))
+        torch.cuda.current_stream().wait_stream(side5)
+        g5.replay()
+        torch.cuda.synchronize()
+        c5["graph_replay"] = rate5(_events(torch, g5.replay, reps))
+    except Exception as e:
+        c5["graph_replay"] = {"error": repr(e)}
+    return c5
 
 
 def side_measurements(torch, pb, W, dev, stream, cfg, toks, offs, tree, info, logp, d_logp, ot, achieved,
@@ -398,57 +472,7 @@ def side_measurements(torch, pb, W, dev, stream, cfg, toks, offs, tree, info, lo
     extra["pb_score_v8192_with_eos"] = {"B1024_uniform_states": score_rate(tree5e, st_uni, 1024),
                                         "B1024_trajectory_states": score_rate(tree5e, st_traj, 1024)}
     del lp5, pool_sc, pool_nx
-    # ---- config 5 greedy decode (V = 8192, blank-free, B = 256, 200 steps): the per-step shape that moves 8 MiB
-    T5, B5 = cfg5.steps, cfg5.batch
-    logp5 = W.make_logp(cfg5)
-    d_lp5 = torch.from_numpy(logp5).to(dev)
-    z5 = torch.zeros(B5, dtype=torch.int32, device=dev)
-    o5b = [torch.empty((T5, B5), dtype=torch.int32, device=dev) for _ in range(2)] + \
-        [torch.empty((T5, B5), dtype=torch.float32, device=dev)]
-    bytes5 = T5 * B5 * (4 * V5 + 12) + 4 * B5
-
-    def rate5(ms):
-        return {"ms": ms, "us_per_frame": ms * 1e3 / T5, "hyp_frames_per_s": B5 * T5 / (ms * 1e-3),
-                "GBps": bytes5 / (ms * 1e-3) / 1e9, "frac_hbm": bytes5 / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
-
-    c5 = {"workload": "config 5: greedy, 20000 phrases of 2-8 Zipf(1.1) tokens, V=8192, blank-free, alpha=0.5, "
-                      "B=256, 200 steps, N(0,3) log-softmax logits (1.6 GiB of log-probs, read once per decode)"}
-    fn = lambda: pb.pb_fuse_frames(tree5, d_lp5, B5 * V5, V5, z5, cfg5.alpha, T5, B5, o5b[0], o5b[1], o5b[2], stream)
-    fn()
-    c5["pb_fuse_frames"] = rate5(_events(torch, fn, 5))
-    w5 = None
-    if ot is not None:
-        ot5 = OracleTree(t5, o5, V5, cfg5.blank_id)
-        w5 = ot5.fuse_frames(logp5, np.zeros(B5, np.int32), cfg5.alpha)
-        c5["pb_fuse_frames"]["parity"] = _same(o5b, w5)
-
-    def per_launch5(sp):
-        prev = z5
-        for t in range(T5):
-            pb.pb_fuse_step(tree5, d_lp5[t], V5, prev, cfg5.alpha, B5, o5b[0][t], o5b[1][t], o5b[2][t], sp)
-            prev = o5b[1][t]
-
-    o5b[0].fill_(-9)
-    per_launch5(stream)
-    torch.cuda.synchronize()
-    c5["per_launch"] = rate5(_events(torch, lambda: per_launch5(stream), 3))
-    if w5 is not None:
-        c5["per_launch"]["parity"] = _same(o5b, w5)
-    try:
-        g5 = torch.cuda.CUDAGraph()
-        side5 = torch.cuda.Stream()
-        side5.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side5):
-            with torch.cuda.graph(g5, stream=side5):
-                per_launch5(int(side5.cuda_stream))
-        torch.cuda.current_stream().wait_stream(side5)
-        g5.replay()
-        torch.cuda.synchronize()
-        c5["graph_replay"] = rate5(_events(torch, g5.replay, 5))
-    except Exception as e:
-        c5["graph_replay"] = {"error": repr(e)}
-    extra["config5_greedy"] = c5
-    del d_lp5, logp5
+    extra["config5_greedy"] = config5_greedy(torch, pb, W, dev, stream, tree5, t5, o5, ot is not None)
     # ---- the EOS rule on the step calls (Sec. II-C, the AED decoder's shape): V = 1024, greedy and beam 3
     eos = V - 1
     toks_e = np.where(toks == eos, 1, toks).astype(np.int32)

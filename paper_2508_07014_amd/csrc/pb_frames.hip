@@ -869,7 +869,10 @@ int launch_step_wave(const DeviceTree& t, const TreePick& pick, const float* d_l
   if (t.vocab_size > kChunk)
     return launch_step_wide(t, pick, d_logp, row_stride, d_states_in, d_last, alpha, B, sel, d_tokens, d_states_out,
                             d_scores, stream);
-  const int waves = B >= 1024 ? 4 : 1;  // few rows: spread them over as many CUs as possible
+#ifndef PB_STEP_WAVES
+#define PB_STEP_WAVES 1
+#endif
+  const int waves = B >= 1024 ? 4 : PB_STEP_WAVES;  // few rows: spread them over as many CUs as possible
   const dim3 grid(static_cast<unsigned>((B + waves - 1) / waves)), block(static_cast<unsigned>(64 * waves));
   const size_t lds = static_cast<size_t>(waves) * kWaveLdsBytes;
   const bool full = t.vocab_size == kChunk;

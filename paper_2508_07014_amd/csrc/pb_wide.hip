@@ -219,11 +219,12 @@ __device__ __forceinline__ FrameOut slow_frame(const TreeView& t, const Cursor& 
 }
 
 // Decides a frame whose base winner (M, vb) over all tokens is known: the arcs of the failure chain against it.
-//   early: arc number `lane` of the state (clamped into its arc range), requested before the row pass
+//   early: arc number `lane` of the state (clamped into its arc range), requested before the row pass, and
+//   early_x: the log-prob of that arc's token, gathered during the pass
 //   last:  label of the previous frame (SEL == 2; any value outside [0, V) = none)
 template <bool FULL, int SEL>
 __device__ __forceinline__ FrameOut decide_wide(const TreeView& t, const Cursor& cur, const float* __restrict__ rowp,
-                                                float alpha, float M, int vb, const ArcRec& early, int last,
+                                                float alpha, float M, int vb, const ArcRec& early, float early_x, int last,
                                                 unsigned* tags, int tag_words, int nch, int lane) {
   const Rec rec0 = cur.rec;
   const bool chain = cur.s != 0;
@@ -240,9 +241,11 @@ __device__ __forceinline__ FrameOut decide_wide(const TreeView& t, const Cursor&
         const int j = j0 + lane;
         const bool valid = j < r.count;
         ArcRec a = early;
-        if (level != 0 || j0 != 0) a = t.arc[r.begin + min(j, r.count - 1)];
+        float xv = early_x;
+        const bool first = level == 0 && j0 == 0;
+        if (!first) a = t.arc[r.begin + min(j, r.count - 1)];
         const int tk = valid ? a.token : 0;  // an unused entry may hold anything: keep the indices in range
-        const float xv = rowp[tk];
+        if (!first) xv = rowp[tk];
         bool shadowed = !valid;
         if (multi) {
           if (level > 0) shadowed = shadowed || tag_test(tags, tk);  // a deeper chain state owns this token
@@ -454,9 +457,10 @@ __device__ __forceinline__ bool run_frames_wide(const TreeView& t, const float* 
     const ArcRec early = t.arc[cur.rec.begin + max(0, min(lane, cur.rec.count - 1))];
     LaneBest fb = lane_best_init(), rb = lane_best_init(), gb = lane_best_init();
     const float* rpn = more ? rp + frame_stride : rp;
+    float early_x = 0.0f;  // log-prob of the early arc's token: gathered after the first turn of the ring, when the arc is there
     auto pass = [&](auto track_c) {
       constexpr bool TRACK = decltype(track_c)::value;
-      for (int g = 0; g < nchp; g += kRing) {
+      auto turn = [&](int g) {  // one turn of the ring: kRing chunks, straight-line code
 #pragma unroll
         for (int u = 0; u < kRing; ++u) {
           const int ch = g + u;
@@ -471,7 +475,11 @@ __device__ __forceinline__ bool run_frames_wide(const TreeView& t, const float* 
           wide_chunk<SEL, TRACK>(xb[u], rw, ch, cur.p_root, alpha, fb, rb, gb);
           __builtin_amdgcn_sched_barrier(0);  // (the four turns would otherwise be interleaved and run out of registers)
         }
-      }
+      };
+      turn(0);
+      // the early arc is there by now: the log-prob of its token is gathered while the rest of the row streams
+      early_x = rp[lane < cur.rec.count ? early.token : 0];
+      for (int g = kRing; g < nchp; g += kRing) turn(g);
     };
     if (track) {
       pass(std::integral_constant<bool, true>{});
@@ -494,7 +502,7 @@ __device__ __forceinline__ bool run_frames_wide(const TreeView& t, const float* 
       }
     }
     if (!stage1) {
-      o = decide_wide<FULL, SEL>(t, cur, rp, alpha, M, uniform_i(vb), early, last, tags, tag_words, nch, lane);
+      o = decide_wide<FULL, SEL>(t, cur, rp, alpha, M, uniform_i(vb), early, early_x, last, tags, tag_words, nch, lane);
       advance(t, cur, o, more);
     }
     const int word = cur.s;
@@ -670,6 +678,8 @@ __global__ void __launch_bounds__(1024) step_wide_kernel(DeviceTree dt, TreePick
   } else {
     p_root = t.p_root[s];
   }
+  float early_x = 0.0f;  // (wave 0: the log-prob of its early arc's token, requested before the row is looked at)
+  if (wave == 0) early_x = rowp[lane < cur.rec.count ? early.token : 0];
   LaneBest fb = lane_best_init(), rb = lane_best_init(), gb = lane_best_init();
   wide_chunk<SEL, false>(x, rw, wave, p_root, alpha, fb, rb, gb);
   StepPart mine_part{0.0f, 0.0f, 0, 0};
@@ -683,6 +693,7 @@ __global__ void __launch_bounds__(1024) step_wide_kernel(DeviceTree dt, TreePick
   const StepPart q = part[have ? lane : 0];
   const float M = ukey_val(wave_max_u(have ? ukey(q.M) : 0u));
   const int vb = __builtin_amdgcn_readlane(q.vb, first_lane(__ballot(have && q.M == M)));
+  const int vb_next = t.root_next[vb];  // where the base winner leads, requested before the arcs are evaluated
   int last = -1;
   if (SEL == 2 && last_in != nullptr) last = uniform_i(last_in[b]);
   FrameOut o;
@@ -697,8 +708,12 @@ __global__ void __launch_bounds__(1024) step_wide_kernel(DeviceTree dt, TreePick
   }
   if (!stage1) {
     unsigned* tags = reinterpret_cast<unsigned*>(lds);
-    o = decide_wide<FULL, SEL>(t, cur, rowp, alpha, M, vb, early, last, tags, nch * kTagWords, nch, lane);
-    advance(t, cur, o, false);
+    o = decide_wide<FULL, SEL>(t, cur, rowp, alpha, M, vb, early, early_x, last, tags, nch * kTagWords, nch, lane);
+    if (!o.arc && o.tok == vb && vb != t.blank && vb != t.eos) {
+      cur.s = uniform_i(vb_next);  // only the state id leaves the kernel
+    } else {
+      advance(t, cur, o, false);
+    }
   }
   if (lane == 0) {
     tokens[b] = o.tok;
