@@ -19,6 +19,9 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
     # packed-fp32 instructions stay off: some of their forms have given wrong results on the test machines
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the leading scalar and pointer arguments of a kernel are in registers when its waves start (the single-step
+    # kernels are a few dependent memory accesses long; the fetch of the argument block was one of them)
+    "-mllvm", "-amdgpu-kernarg-preload-count=16",
     "-Wall", "-Wextra", "-Wno-unused-parameter",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]

@@ -172,7 +172,7 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
         }
         hit_vb = hit_vb || (valid && tk == vb);
         const float fa = __fadd_rn(row[tk], __fmul_rn(alpha, __fadd_rn(p, a.score)));
-        const bool take = !shadowed && (fa > bf || (fa == bf && tk < btok));
+        const bool take = !shadowed & ((fa > bf) | ((fa == bf) & (tk < btok)));  // (no short-circuit: no branches)
         bf = take ? fa : bf;
         btok = take ? tk : btok;
         bchild = take ? child : bchild;
@@ -680,27 +680,68 @@ __global__ void __launch_bounds__(512) frames_fix_kernel(DeviceTree dt, TreePick
 #endif
 }
 
-// Single step: one wave per hypothesis, no speculation.  With a table of trees every hypothesis names its own.
-template <bool FULL, int SEL>
-__global__ void __launch_bounds__(256) step_wave_kernel(DeviceTree dt, TreePick pick, const float* __restrict__ logp,
-                                                        int64_t row_stride, const int32_t* __restrict__ states_in,
-                                                        const int32_t* __restrict__ last_in, float alpha, int B,
-                                                        int32_t* __restrict__ tokens, int32_t* __restrict__ states_out,
-                                                        float* __restrict__ scores) {
+// Single step: one wave per hypothesis, no speculation.  A step is a handful of dependent memory accesses long
+// (arguments -> state id -> state record -> arcs -> record of the winner's target), so what the kernel costs is
+// set by the order of its requests: the row, the root scores and the state id are requested together before
+// anything is waited for, then the state's record, accumulated backoff and EOS boost together, then the arcs.
+// LEAN: one wave per workgroup and one tree for all rows -- the grid is exactly B, no argument has to arrive
+// before the requests go out and nothing but the hypothesis index separates the waves; used for small batches,
+// where the call is latency-bound.  Otherwise four waves per workgroup, with a table of trees when every
+// hypothesis names its own.
+template <bool FULL, int SEL, bool LEAN>
+__global__ void __launch_bounds__(LEAN ? 64 : 256) step_wave_kernel(
+    const float* __restrict__ logp, int64_t row_stride, const int32_t* __restrict__ states_in,
+    const float* __restrict__ root_score, const int32_t* __restrict__ last_in, float alpha, int B,
+    int32_t* __restrict__ tokens, int32_t* __restrict__ states_out, float* __restrict__ scores, DeviceTree dt,
+    TreePick pick) {
   extern __shared__ float lds[];
-  const int lane = threadIdx.x & 63, wave = uniform_i(threadIdx.x >> 6);
-  const int b = blockIdx.x * (blockDim.x >> 6) + wave;
-  if (b >= B) return;
+  const int lane = threadIdx.x & 63, wave = LEAN ? 0 : uniform_i(threadIdx.x >> 6);
+  const int b = LEAN ? static_cast<int>(blockIdx.x) : static_cast<int>(blockIdx.x * (blockDim.x >> 6)) + wave;
+  if (!LEAN && b >= B) return;
   float* row = lds + wave * kWaveLdsFloats;
   unsigned* tags = reinterpret_cast<unsigned*>(row + kChunk);
   DeviceTree mine = dt;
-  const bool tree_ok = pick_tree(pick, b, mine);
+  bool tree_ok = true;
+  if constexpr (!LEAN) tree_ok = pick_tree(pick, b, mine);
   const TreeView t = make_view(mine);
-  const int s = tree_ok ? states_in[b] : -1;  // an unknown tree marks the hypothesis like an invalid state
+  constexpr int kEarlyBatches = SEL == 0 ? 4 : 2, kEarlyBatches1 = SEL == 0 ? 4 : (SEL == 1 ? 2 : 0);
+  float x[16], c[16];
+  // (loads retire in order: the root scores come from a cache and are worked on while the row is on its way)
+  // (`root_score` is the tree's array again, as an argument of its own: the leading arguments are in registers
+  // when the wave starts, the tree structure has to be fetched)
+  load16<FULL>(LEAN ? root_score : t.root_score, 0, t.V, lane, 0.0f, c);
+  load16<FULL>(logp + static_cast<size_t>(b) * row_stride, 0, t.V, lane, -INFINITY, x);
+  int s = tree_ok ? states_in[b] : -1;  // an unknown tree marks the hypothesis like an invalid state
   int last = -1;
   if (SEL == 2 && last_in != nullptr) last = last_in[b];
-  run_frames_1k<false, FULL, SEL, false>(t, logp, 0, row_stride, alpha, B, b, 0, 1, s, last, 1, nullptr, nullptr, 0, tokens,
-                                         states_out, scores, row, tags, lane);
+  __builtin_amdgcn_sched_barrier(0);  // (all of the above is in flight before the first wait)
+  s = uniform_i(s);
+  last = uniform_i(last);
+  // An invalid state is decoded as the root and marked at the end: an early exit here would let the compiler
+  // move the row requests behind the test, i.e. behind the wait for the state id.
+  const bool ok = valid_state(t, s);
+  if (!LEAN && !ok) {
+    if (lane == 0) {
+      tokens[b] = -1;
+      states_out[b] = -1;
+      scores[b] = NAN;
+    }
+    return;
+  }
+  Cursor cur = cursor_at(t, ok ? s : 0);
+  __builtin_amdgcn_sched_barrier(0);  // (the three parts of the cursor are requested together)
+  float c_p = cur.p_root;
+  make_base_boost<SEL>(0, lane, t.blank, c_p, alpha, c, c);  // element-wise, in place
+  float val;
+  int tok;
+  bool row_in_lds = false;
+  frame_1k<FULL, SEL, kEarlyBatches, kEarlyBatches1, 4>(t, cur, x, c, c_p, alpha, row, tags, lane, last, false, [] {},
+                                                        val, tok, row_in_lds);
+  if (lane == 0) {
+    tokens[b] = ok ? tok : -1;
+    states_out[b] = ok ? cur.s : -1;
+    scores[b] = ok ? val : NAN;
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -711,20 +752,32 @@ __global__ void __launch_bounds__(256) step_wave_kernel(DeviceTree dt, TreePick 
 // score and extracts its K best totals in order by repeated wave arg-max (a taken entry becomes
 // NaN, which no maximum or equality test selects).  The K*K survivors meet in LDS, and wave 0
 // picks the utterance's K best by (total descending, flat index k*V+v ascending).
+// A step is latency-bound, so the requests go out in the order of the single greedy step: root scores, row,
+// states and hypothesis score before the first wait; an utterance with an invalid state is decoded from the
+// root and marked at the end, so that no early exit separates the wave start from the requests.  The raw row
+// goes into the overlay first: an arc then finds its log-prob in LDS instead of in memory.
 constexpr int kBeamWaveMaxK = 8;
 constexpr int kBeamWaveLdsFloats = 2 * kChunk + kTagWords;                   // overlay values, overlay children, marks
 constexpr size_t kBeamCandBytes = kBeamWaveMaxK * kBeamWaveMaxK * 3 * sizeof(int);  // value, flat index, child
 
 template <bool FULL>
 __global__ void __launch_bounds__(64 * kBeamWaveMaxK) beam_wave_kernel(
-    DeviceTree dt, const float* __restrict__ logp, int64_t row_stride, const float* __restrict__ hyp,
-    const int32_t* __restrict__ states_in, float alpha, int K, int32_t* __restrict__ tokens,
-    int32_t* __restrict__ parents, int32_t* __restrict__ states_out, float* __restrict__ scores_out) {
+    const float* __restrict__ logp, int64_t row_stride, const float* __restrict__ hyp,
+    const int32_t* __restrict__ states_in, const float* __restrict__ root_score, float alpha, int K,
+    int32_t* __restrict__ tokens, int32_t* __restrict__ parents, int32_t* __restrict__ states_out,
+    float* __restrict__ scores_out, DeviceTree dt) {
   extern __shared__ float lds[];
   const int lane = threadIdx.x & 63, wave = uniform_i(threadIdx.x >> 6);
   const int u = blockIdx.x, h = u * K + wave;
   const TreeView t = make_view(dt);
   const int V = t.V;
+  const float* lrow = logp + static_cast<size_t>(h) * row_stride;
+  float x[16], c[16];
+  load16<FULL>(root_score, 0, V, lane, 0.0f, c);  // (the tree's array, as a leading argument: in registers at the start)
+  load16<FULL>(lrow, 0, V, lane, -INFINITY, x);
+  const int sk = states_in[u * K + min(lane, K - 1)];  // every wave sees all K states
+  const float hs_in = hyp[h];
+  __builtin_amdgcn_sched_barrier(0);  // (all of the above is in flight before the first wait)
   float* cand_val = lds;  // [K*K], then the flat indices and the children
   int* cand_idx = reinterpret_cast<int*>(lds + kBeamWaveMaxK * kBeamWaveMaxK);
   int* cand_nxt = cand_idx + kBeamWaveMaxK * kBeamWaveMaxK;
@@ -732,25 +785,15 @@ __global__ void __launch_bounds__(64 * kBeamWaveMaxK) beam_wave_kernel(
   int* ov_next = reinterpret_cast<int*>(ov + kChunk);
   unsigned* tags = reinterpret_cast<unsigned*>(ov + 2 * kChunk);
 
-  // an utterance with an invalid state is marked as a whole; every wave sees all K states
-  const int sk = states_in[u * K + min(lane, K - 1)];
-  if (__ballot(!valid_state(t, sk)) != 0) {
-    if (wave == 0 && lane < K) {
-      tokens[u * K + lane] = -1;
-      parents[u * K + lane] = -1;
-      states_out[u * K + lane] = -1;
-      scores_out[u * K + lane] = NAN;
-    }
-    return;
-  }
-  const int s = uniform_i(states_in[h]);
-  const float hs = uniform_f(hyp[h]);
-  const float* lrow = logp + static_cast<size_t>(h) * row_stride;
-  float x[16], c[16];
-  load16<FULL>(lrow, 0, V, lane, -INFINITY, x);
+  // an utterance with an invalid state is marked as a whole (at the end)
+  const bool bad = __ballot(!valid_state(t, sk)) != 0;
+  const int s = bad ? 0 : __builtin_amdgcn_readlane(sk, wave);
+  const float hs = uniform_f(hs_in);
   const Cursor cur = cursor_at(t, s);
-  rebuild_base_boost<FULL, 0>(t, lane, cur.p_root, alpha, c);
+  __builtin_amdgcn_sched_barrier(0);  // (the parts of the cursor are requested together)
+  make_base_boost<0>(0, lane, t.blank, cur.p_root, alpha, c, c);  // element-wise, in place
   tags_clear(tags, lane);
+  store_row_lds(ov, lane, x);  // the raw row: an arc reads its log-prob here and puts its fused value in its place
   // ---- overlay: arcs of the failure chain, deepest state first ------------------------------------
   {
     float p = 0.0f;
@@ -760,7 +803,7 @@ __global__ void __launch_bounds__(64 * kBeamWaveMaxK) beam_wave_kernel(
         const ArcRec a = t.arc[r.begin + j];
         if (!tag_test(tags, a.token)) {  // tokens of one state are distinct: no lane races for an entry
           tag_set(tags, a.token);
-          ov[a.token] = __fadd_rn(lrow[a.token], __fmul_rn(alpha, __fadd_rn(p, a.score)));
+          ov[a.token] = __fadd_rn(ov[a.token], __fmul_rn(alpha, __fadd_rn(p, a.score)));
           ov_next[a.token] = r.begin + j + 1;
         }
       }
@@ -821,10 +864,10 @@ __global__ void __launch_bounds__(64 * kBeamWaveMaxK) beam_wave_kernel(
     const float M = ukey_val(wave_max_u(live ? ukey(val) : 0u));
     const int best = wave_min_nn((live && val == M) ? idx : INT_MAX);
     if (live && idx == best) {
-      tokens[u * K + j] = idx % V;
-      parents[u * K + j] = idx / V;
-      states_out[u * K + j] = nxt;
-      scores_out[u * K + j] = val;
+      tokens[u * K + j] = bad ? -1 : idx % V;
+      parents[u * K + j] = bad ? -1 : idx / V;
+      states_out[u * K + j] = bad ? -1 : nxt;
+      scores_out[u * K + j] = bad ? NAN : val;
       live = false;
     }
   }
@@ -869,18 +912,24 @@ int launch_step_wave(const DeviceTree& t, const TreePick& pick, const float* d_l
   if (t.vocab_size > kChunk)
     return launch_step_wide(t, pick, d_logp, row_stride, d_states_in, d_last, alpha, B, sel, d_tokens, d_states_out,
                             d_scores, stream);
-#ifndef PB_STEP_WAVES
-#define PB_STEP_WAVES 1
-#endif
-  const int waves = B >= 1024 ? 4 : PB_STEP_WAVES;  // few rows: spread them over as many CUs as possible
+  // Few rows: one wave per workgroup, spread over as many CUs as there are rows (the call is latency-bound).
+  const bool lean = pick.table == nullptr && B < 1024;
+  const int waves = lean ? 1 : 4;
   const dim3 grid(static_cast<unsigned>((B + waves - 1) / waves)), block(static_cast<unsigned>(64 * waves));
   const size_t lds = static_cast<size_t>(waves) * kWaveLdsBytes;
   const bool full = t.vocab_size == kChunk;
-#define PB_LAUNCH(FULL, SEL)                                                                                      \
-  hipLaunchKernelGGL((step_wave_kernel<FULL, SEL>), grid, block, lds, stream, t, pick, d_logp, row_stride,       \
-                     d_states_in, d_last, alpha, B, d_tokens, d_states_out, d_scores)
+#define PB_STEP(FULL, SEL, LEAN)                                                                                   \
+  hipLaunchKernelGGL((step_wave_kernel<FULL, SEL, LEAN>), grid, block, lds, stream, d_logp, row_stride,            \
+                     d_states_in, t.root_score, d_last, alpha, B, d_tokens, d_states_out, d_scores, t, pick)
+#define PB_LAUNCH(FULL, SEL)   \
+  if (lean) {                  \
+    PB_STEP(FULL, SEL, true);  \
+  } else {                     \
+    PB_STEP(FULL, SEL, false); \
+  }
   PB_DISPATCH(full, sel, PB_LAUNCH)
 #undef PB_LAUNCH
+#undef PB_STEP
   return hipGetLastError() == hipSuccess ? PB_OK : PB_EHIP;
 }
 
@@ -966,11 +1015,11 @@ int launch_beam_wave(const DeviceTree& t, const float* d_logp, int64_t row_strid
   const size_t lds = kBeamCandBytes + static_cast<size_t>(K) * kBeamWaveLdsFloats * sizeof(float);
   const dim3 grid(static_cast<unsigned>(U)), block(static_cast<unsigned>(64 * K));
   if (t.vocab_size == kChunk)
-    hipLaunchKernelGGL(beam_wave_kernel<true>, grid, block, lds, stream, t, d_logp, row_stride, d_hyp, d_states_in,
-                       alpha, K, d_tokens, d_parents, d_states_out, d_scores_out);
+    hipLaunchKernelGGL(beam_wave_kernel<true>, grid, block, lds, stream, d_logp, row_stride, d_hyp, d_states_in,
+                       t.root_score, alpha, K, d_tokens, d_parents, d_states_out, d_scores_out, t);
   else
-    hipLaunchKernelGGL(beam_wave_kernel<false>, grid, block, lds, stream, t, d_logp, row_stride, d_hyp, d_states_in,
-                       alpha, K, d_tokens, d_parents, d_states_out, d_scores_out);
+    hipLaunchKernelGGL(beam_wave_kernel<false>, grid, block, lds, stream, d_logp, row_stride, d_hyp, d_states_in,
+                       t.root_score, alpha, K, d_tokens, d_parents, d_states_out, d_scores_out, t);
   return hipGetLastError() == hipSuccess ? PB_OK : PB_EHIP;
 }
 

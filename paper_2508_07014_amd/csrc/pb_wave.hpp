@@ -239,7 +239,15 @@ __device__ __forceinline__ void tags_clear(unsigned* bits, int lane) {
 __device__ __forceinline__ void tag_set(unsigned* bits, int tk) { atomicOr(&bits[tk >> 5], 1u << (tk & 31)); }
 __device__ __forceinline__ bool tag_test(const unsigned* bits, int tk) { return ((bits[tk >> 5] >> (tk & 31)) & 1u) != 0u; }
 
-__device__ __forceinline__ float max4(float a, float b, float c, float d) { return fmaxf(fmaxf(a, b), fmaxf(c, d)); }
+// Maximum of four values in two instructions.  Written out because the compiler puts a canonicalising
+// max(x, x) in front of every operand of fmaxf whose origin it cannot see, which doubles the count; the
+// instructions return the other operand when one is a NaN, as fmaxf does.
+__device__ __forceinline__ float max4(float a, float b, float c, float d) {
+  float m;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(m) : "v"(a), "v"(b), "v"(c));
+  asm("v_max_f32 %0, %1, %2" : "=v"(m) : "v"(m), "v"(d));
+  return m;
+}
 
 // Stage 1 of the two-stage rule on one chunk: the unboosted row maximum and its lowest token.
 __device__ __forceinline__ void plain_argmax(const float (&x)[16], int lane, float& M0, int& v0) {

@@ -539,14 +539,17 @@ __device__ __forceinline__ bool run_frames_wide(const TreeView& t, const float* 
 
 // Root scores of a row for the pass over it: zero beyond V, NaN in the blank and EOS columns (those two tokens
 // are candidates of their own, see special_candidate).
-__device__ __forceinline__ float4 staged_root_scores(const TreeView& t, int i) {
-  float4 q = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-  if (i < t.V) q = *reinterpret_cast<const float4*>(t.root_score + i);  // V % 4 == 0
+__device__ __forceinline__ float4 mask_special(const TreeView& t, int i, float4 q) {
   float e[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
   for (int k = 0; k < 4; ++k)
     if (i + k == t.blank || i + k == t.eos) e[k] = NAN;
   return make_float4(e[0], e[1], e[2], e[3]);
+}
+__device__ __forceinline__ float4 staged_root_scores(const TreeView& t, int i) {
+  float4 q = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+  if (i < t.V) q = *reinterpret_cast<const float4*>(t.root_score + i);  // V % 4 == 0
+  return mask_special(t, i, q);
 }
 
 // The same into LDS for a whole row, by the whole workgroup; ends with a barrier.
@@ -637,36 +640,48 @@ struct StepPart {
   int vb, v0;
 };
 
-template <bool FULL, int SEL>
-__global__ void __launch_bounds__(1024) step_wide_kernel(DeviceTree dt, TreePick pick, const float* __restrict__ logp,
-                                                         int64_t row_stride, const int32_t* __restrict__ states_in,
-                                                         const int32_t* __restrict__ last_in, float alpha, int B,
-                                                         int32_t* __restrict__ tokens, int32_t* __restrict__ states_out,
-                                                         float* __restrict__ scores) {
+// (The order of the requests is what a single step costs: the root scores, which sit in a cache, and the row go out
+// first, with the state id, before anything is waited for.  LEAN: one tree for all rows; the leading arguments,
+// the root-score array among them, are then in registers when the wave starts, and an invalid state is decoded as
+// the root and marked at the end, so that no early exit stands between the wave start and the requests.)
+template <bool FULL, int SEL, bool LEAN>
+__global__ void __launch_bounds__(1024) step_wide_kernel(
+    const float* __restrict__ logp, int64_t row_stride, const int32_t* __restrict__ states_in,
+    const float* __restrict__ root_score, const int32_t* __restrict__ last_in, float alpha, int B,
+    int32_t* __restrict__ tokens, int32_t* __restrict__ states_out, float* __restrict__ scores, DeviceTree dt,
+    TreePick pick) {
   extern __shared__ float lds[];  // wave 0's token marks
   __shared__ StepPart part[16];
   const int lane = threadIdx.x & 63, wave = uniform_i(threadIdx.x >> 6), nwaves = blockDim.x >> 6;
   const int b = blockIdx.x;
   DeviceTree mine = dt;
-  const bool tree_ok = pick_tree(pick, b, mine);
+  bool tree_ok = true;
+  if constexpr (!LEAN) tree_ok = pick_tree(pick, b, mine);
   const TreeView t = make_view(mine);
   const int nch = nwaves;  // launched with one wave per chunk
   const float* rowp = logp + static_cast<size_t>(b) * row_stride;
+  const float* rsp = LEAN ? root_score : t.root_score;
   float x[16], rw[16];
+  load16<FULL>(rsp, wave * kChunk, t.V, lane, 0.0f, rw);
   load16<FULL>(rowp, wave * kChunk, t.V, lane, -INFINITY, x);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const float4 q = staged_root_scores(t, wave * kChunk + 256 * i + 4 * lane);
-    rw[4 * i + 0] = q.x; rw[4 * i + 1] = q.y; rw[4 * i + 2] = q.z; rw[4 * i + 3] = q.w;
-  }
-  const int s = tree_ok ? uniform_i(states_in[b]) : -1;  // an unknown tree marks the hypothesis like an invalid state
-  if (!valid_state(t, s)) {  // uniform over the workgroup
+  int s = tree_ok ? states_in[b] : -1;  // an unknown tree marks the hypothesis like an invalid state
+  __builtin_amdgcn_sched_barrier(0);
+  s = uniform_i(s);
+  const bool ok = valid_state(t, s);  // uniform over the workgroup
+  if (!LEAN && !ok) {
     if (threadIdx.x == 0) {
       tokens[b] = -1;
       states_out[b] = -1;
       scores[b] = NAN;
     }
     return;
+  }
+  if (!ok) s = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {  // NaN in the blank and EOS columns: those two are candidates of their own
+    const float4 q = mask_special(t, wave * kChunk + 256 * i + 4 * lane,
+                                  make_float4(rw[4 * i], rw[4 * i + 1], rw[4 * i + 2], rw[4 * i + 3]));
+    rw[4 * i + 0] = q.x; rw[4 * i + 1] = q.y; rw[4 * i + 2] = q.z; rw[4 * i + 3] = q.w;
   }
   Cursor cur;
   ArcRec early = ArcRec{0, 0.0f};
@@ -716,9 +731,9 @@ __global__ void __launch_bounds__(1024) step_wide_kernel(DeviceTree dt, TreePick
     }
   }
   if (lane == 0) {
-    tokens[b] = o.tok;
-    states_out[b] = cur.s;
-    scores[b] = o.val;
+    tokens[b] = ok ? o.tok : -1;
+    states_out[b] = ok ? cur.s : -1;
+    scores[b] = ok ? o.val : NAN;
   }
 }
 
@@ -751,11 +766,19 @@ int launch_step_wide(const DeviceTree& t, const TreePick& pick, const float* d_l
   const bool full = V % kChunk == 0;
   const size_t lds = static_cast<size_t>(nch) * kTagWords * sizeof(unsigned);
   const dim3 grid(static_cast<unsigned>(B)), block(static_cast<unsigned>(64 * nch));
-#define PB_LAUNCH(FULL, SEL)                                                                                       \
-  hipLaunchKernelGGL((step_wide_kernel<FULL, SEL>), grid, block, lds, stream, t, pick, d_logp, row_stride,        \
-                     d_states_in, d_last, alpha, B, d_tokens, d_states_out, d_scores)
+  const bool lean = pick.table == nullptr;
+#define PB_STEP(FULL, SEL, LEAN)                                                                                   \
+  hipLaunchKernelGGL((step_wide_kernel<FULL, SEL, LEAN>), grid, block, lds, stream, d_logp, row_stride,            \
+                     d_states_in, t.root_score, d_last, alpha, B, d_tokens, d_states_out, d_scores, t, pick)
+#define PB_LAUNCH(FULL, SEL)   \
+  if (lean) {                  \
+    PB_STEP(FULL, SEL, true);  \
+  } else {                     \
+    PB_STEP(FULL, SEL, false); \
+  }
   PB_DISPATCH(full, sel, PB_LAUNCH)
 #undef PB_LAUNCH
+#undef PB_STEP
   return hipGetLastError() == hipSuccess ? PB_OK : PB_EHIP;
 }
 
