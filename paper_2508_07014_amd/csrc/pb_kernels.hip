@@ -35,15 +35,21 @@ __device__ __forceinline__ float scatter_chain(const DeviceTree& t, int s, int v
   float p = 0.0f;
   int x = s;
   while (x != 0) {
+    // One record holds the state and the state its failure link leads to: the arcs of both levels are requested
+    // in one sweep (two chain levels per pair of dependent accesses instead of one).
     const StateRec r = t.state[x];
-    for (int j = threadIdx.x; j < r.arc_count; j += blockDim.x) {
-      const ArcRec a = t.arc[r.arc_begin + j];
+    const int c0 = r.arc_count, c1 = r.fail != 0 ? r.f_arc_count : 0;
+    const float p1 = __fadd_rn(p, r.backoff);
+    for (int j = threadIdx.x; j < c0 + c1; j += blockDim.x) {
+      const bool second = j >= c0;
+      const int idx = second ? r.f_arc_begin + (j - c0) : r.arc_begin + j;
+      const ArcRec a = t.arc[idx];
       const unsigned rel = static_cast<unsigned>(a.token - v0);
-      if (rel < static_cast<unsigned>(n))
-        atomicMax(&row[rel], pack_entry(r.arc_begin + j + 1, __fadd_rn(p, a.score)));
+      if (rel < static_cast<unsigned>(n)) atomicMax(&row[rel], pack_entry(idx + 1, __fadd_rn(second ? p1 : p, a.score)));
     }
-    p = __fadd_rn(p, r.backoff);
-    x = r.fail;
+    if (r.fail == 0) return p1;
+    p = __fadd_rn(p1, r.f_backoff);
+    x = r.f_fail;
   }
   return p;
 }
