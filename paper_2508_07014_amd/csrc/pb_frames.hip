@@ -540,6 +540,7 @@ __device__ __forceinline__ bool run_frames_1k(const TreeView& t, const float* __
   using std::integral_constant;
   int fb = f0;
   for (; fb + NB <= f1; fb += NB) {  // whole turns of the ring: straight-line code
+    if (GUESS) set_wave_priority(min(3, 4 * (f1 - fb) / (f1 - f0)));  // (pass 1: the more is left, the higher)
     if (do_frame(integral_constant<int, 0>{}, integral_constant<bool, true>{}, fb)) return true;
     if (do_frame(integral_constant<int, 1>{}, integral_constant<bool, true>{}, fb + 1)) return true;
     if (do_frame(integral_constant<int, 2>{}, integral_constant<bool, true>{}, fb + 2)) return true;
@@ -573,6 +574,7 @@ __device__ __forceinline__ bool run_frames_1k(const TreeView& t, const float* __
       int npatch = 0;
       if (!certified) {
         // (at most up to the frame before the last one of the next range, whose state word carries that range's own bit)
+        set_wave_priority(3);  // the kernel ends with these waves
         npatch = run_on_1k<FULL, SEL>(t, rp, frame_stride, alpha, cur.s, last, g, glabel, min(kPatchMax, next_len - 1),
                                       patch, row, tags, lane);
         certified = npatch > 0;

@@ -450,6 +450,7 @@ __device__ __forceinline__ bool run_frames_wide(const TreeView& t, const float* 
   Cursor cur = cursor_at(t, s);
   LaneOut out{f0, 0, 0, 0.0f};
   for (int f = f0; f < f1; ++f) {
+    if (GUESS) set_wave_priority(min(3, 4 * (f1 - f) / (f1 - f0)));  // (pass 1: the more is left, the higher)
     const bool more = f + 1 < f1;
     const bool track = guessable && !more && f1 < T;  // last frame of the range: also its root-state winner
     // the first arcs of the state, requested before the pass over the row (unconditionally; the index is
