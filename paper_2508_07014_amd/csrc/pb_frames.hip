@@ -625,7 +625,7 @@ __global__ void __launch_bounds__(256, 4) frames_spec_kernel(DeviceTree dt, Tree
   bool tree_ok = true;
   if constexpr (FOREST) tree_ok = pick_tree(pick, b, mine);  // a table of trees: hypothesis b names its own
   const TreeView t = make_view(mine);
-  const int f0 = j * seg_len, f1 = min(T, f0 + seg_len);
+  const int f0 = seg_begin(j, T, nseg), f1 = seg_begin(j + 1, T, nseg);
   int s = 0, last = -1;
   if (j == 0) {
     s = states0[b];
@@ -635,7 +635,8 @@ __global__ void __launch_bounds__(256, 4) frames_spec_kernel(DeviceTree dt, Tree
   int32_t* patch = nullptr;  // the record of the boundary after this segment
   if (patches != nullptr && f1 < T) patch = patches + (static_cast<size_t>(j) * B + b) * kPatchInts;
   run_frames_1k<false, FULL, SEL, true>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, T, states0,
-                                        patch, min(T, f1 + seg_len) - f1, tokens, states, scores, row, tags, lane);
+                                        patch, (j + 2 <= nseg ? seg_begin(j + 2, T, nseg) : f1) - f1, tokens, states, scores,
+                                        row, tags, lane);
 }
 
 // Pass 2: one workgroup per hypothesis; its waves share the segments j = 1 .. nseg-1.
@@ -664,7 +665,7 @@ __global__ void __launch_bounds__(512) frames_fix_kernel(DeviceTree dt, TreePick
   fix_segments<SEL == 2>(T, B, b, seg_len, nseg, tokens, states, scores, patches, assumed, assumed_tok, bad_words, lane,
                          wave, nwaves,
                          [&](int seg, int s, int last) {
-                           const int f0 = seg * seg_len, f1 = min(T, f0 + seg_len);
+                           const int f0 = seg_begin(seg, T, nseg), f1 = seg_begin(seg + 1, T, nseg);
 #ifdef PB_STATS
                            const long long c0 = wall_clock64();
 #endif

@@ -404,7 +404,7 @@ __device__ __forceinline__ void fix_segments(int T, int B, int b, int seg_len, i
         const int tok = rec[4 + q], st = rec[4 + kPatchMax + q];
         const float sc = __int_as_float(rec[4 + 2 * kPatchMax + q]);
         if (q < count) {
-          const size_t o = static_cast<size_t>(j * seg_len + q) * B + b;
+          const size_t o = static_cast<size_t>(seg_begin(j, T, nseg) + q) * B + b;
           publish_i32(tokens + o, tok);
           publish_i32(states + o, st);
           scores[o] = sc;
@@ -412,13 +412,13 @@ __device__ __forceinline__ void fix_segments(int T, int B, int b, int seg_len, i
       }
     }
   }
-  auto end_word_ptr = [&](int seg) { return states + static_cast<size_t>((seg + 1) * seg_len - 1) * B + b; };
+  auto end_word_ptr = [&](int seg) { return states + static_cast<size_t>(seg_begin(seg + 1, T, nseg) - 1) * B + b; };
   auto end_word_of = [&](int seg) {  // state word of the last frame of segment `seg` (boundary bit included)
     return peek_i32(end_word_ptr(seg));
   };
   auto end_token_of = [&](int seg) {  // label of the last frame of segment `seg`
     if (!WITH_TOKENS) return -1;
-    return peek_i32(tokens + static_cast<size_t>((seg + 1) * seg_len - 1) * B + b);
+    return peek_i32(tokens + static_cast<size_t>(seg_begin(seg + 1, T, nseg) - 1) * B + b);
   };
   // Wave 0 reads the outcome before every segment in one access (lane j: the end of segment j - 1), records
   // it as what segment j is decided from, and publishes the set of segments whose guess is not certified; the

@@ -593,7 +593,7 @@ __global__ void __launch_bounds__(256, 2) wide_spec_kernel(DeviceTree dt, TreePi
     stage_root_scores(t, rs, nchp);
   }
   if (!live) return;
-  const int f0 = j * seg_len, f1 = min(T, f0 + seg_len);
+  const int f0 = seg_begin(j, T, nseg), f1 = seg_begin(j + 1, T, nseg);
   int s = 0, last = -1;
   if (j == 0) {
     s = states0[b];
@@ -627,7 +627,7 @@ __global__ void __launch_bounds__(512) wide_fix_kernel(DeviceTree dt, TreePick p
   fix_segments<SEL == 2>(T, B, b, seg_len, nseg, tokens, states, scores, nullptr, assumed, assumed_tok, bad_words, lane,
                          wave, nwaves,
                          [&](int seg, int s, int last) {
-                           const int f0 = seg * seg_len, f1 = min(T, f0 + seg_len);
+                           const int f0 = seg_begin(seg, T, nseg), f1 = seg_begin(seg + 1, T, nseg);
                            return run_frames_wide<true, FULL, SEL, false>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1,
                                                                    s, last, T, nullptr, tokens, states, scores, rs, tags,
                                                                    nchp, lane);
