@@ -52,11 +52,20 @@ def _load_probe():
     lib.pb_probe_chase.restype = C.c_int
     lib.pb_probe_chase.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
 
+    lib.pb_probe_rowmax.restype = C.c_int
+    lib.pb_probe_rowmax.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+
     def chase(d_table, n, start, hops, d_out, stream):
         rc = lib.pb_probe_chase(d_table.data_ptr(), n, start, hops, d_out.data_ptr(), stream or None)
         if rc != 0:
             raise RuntimeError(f"pb_probe_chase: {rc}")
 
+    def rowmax(d_logp, row_stride, V, d_prev, d_out, B, stream):
+        rc = lib.pb_probe_rowmax(d_logp.data_ptr(), row_stride, V, d_prev.data_ptr(), d_out.data_ptr(), B, stream or None)
+        if rc != 0:
+            raise RuntimeError(f"pb_probe_rowmax: {rc}")
+
+    chase.rowmax = rowmax
     return chase
 
 
@@ -396,6 +405,20 @@ def side_measurements(torch, pb, W, dev, stream, cfg, toks, offs, tree, info, lo
         g0.replay()
         torch.cuda.synchronize()
         extra["graph_replay"]["empty_kernel_us_per_node"] = _events(torch, g0.replay, 5) * 1e3 / frames
+        # ... and the least a greedy step can do: the same rows, one wave per row, arg-max without a tree, every
+        # launch reading what the one before it wrote
+        g1 = torch.cuda.CUDAGraph()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g1, stream=side):
+                prev = d_s0
+                for t in range(frames):
+                    chase.rowmax(d_logp[t], V, V, prev, d_tok[t], B, int(side.cuda_stream))
+                    prev = d_tok[t]
+        torch.cuda.current_stream().wait_stream(side)
+        g1.replay()
+        torch.cuda.synchronize()
+        extra["graph_replay"]["row_argmax_without_tree_us_per_node"] = _events(torch, g1.replay, 5) * 1e3 / frames
     except Exception as e:  # the graph regime is a side measurement; say why it is missing
         extra["graph_replay"] = {"error": repr(e)}
     # ---- the single-step kernel at growing batch (config 3 tree): where it leaves the latency-bound regime.
