@@ -222,6 +222,15 @@ int pb_fuse_frames_ws(const pb_tree* tree, const float* d_logp, int64_t frame_st
                       void* hip_stream);
 
 /*
+ * pb_fuse_frames_plan -- how pb_fuse_frames* would cut the T frames of a call with B hypotheses into segments (host
+ * only, nothing is launched; for tests and for sizing).  Writes the number of segments to *n_segments and, if
+ * `bounds` is not NULL, n_segments + 1 frame indices to it (host array with room for 65 entries): segment j covers
+ * frames bounds[j] .. bounds[j + 1] - 1, bounds[0] = 0, bounds[n_segments] = T; every hypothesis is cut the same way.
+ * T == 0 or B == 0 gives zero segments.  PB_EINVAL for a null tree or n_segments, or negative sizes.
+ */
+int pb_fuse_frames_plan(const pb_tree* tree, int32_t T, int32_t B, int32_t* n_segments, int32_t* bounds);
+
+/*
  * pb_fuse_frames_static -- pb_fuse_frames_ws for callers that cannot allocate device memory (code under HIP
  * graph capture, tight serving loops, harnesses that forbid allocation): the workspace is a fixed array inside
  * the library, 1 MiB per GPU, held from the first pb_build on that GPU until the process ends.  The call

@@ -18,7 +18,8 @@ PB_W_UNIFORM, PB_W_LOGDEPTH, PB_W_UNIFORM_FINAL = 0, 1, 2
 PB_SELECT_FUSED, PB_SELECT_TWO_STAGE, PB_SELECT_TWO_STAGE_CTC = 0, 1, 2
 
 EXPORTS = ["pb_build", "pb_free", "pb_info", "pb_host_arrays", "pb_state_prefix", "pb_score", "pb_fuse_step",
-           "pb_fuse_frames", "pb_fuse_step_select", "pb_fuse_frames_select", "pb_fuse_frames_workspace_bytes",
+           "pb_fuse_frames", "pb_fuse_step_select", "pb_fuse_frames_select", "pb_fuse_frames_plan",
+           "pb_fuse_frames_workspace_bytes",
            "pb_fuse_frames_ws", "pb_fuse_frames_static", "pb_fuse_step_beam", "pb_forest_build", "pb_forest_free", "pb_score_forest",
            "pb_fuse_step_forest", "pb_fuse_frames_forest", "pb_fuse_step_beam_forest", "pb_validate",
            "pb_validate_states", "pb_strerror"]
@@ -93,6 +94,8 @@ def load():
     lib.pb_fuse_frames_select.restype = C.c_int
     lib.pb_fuse_frames_select.argtypes = [vp, vp, C.c_int64, C.c_int64, vp, vp, C.c_float, C.c_int32, C.c_int32,
                                           C.c_int32, vp, vp, vp, vp]
+    lib.pb_fuse_frames_plan.restype = C.c_int
+    lib.pb_fuse_frames_plan.argtypes = [vp, C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.pb_fuse_frames_workspace_bytes.restype = C.c_int64
     lib.pb_fuse_frames_workspace_bytes.argtypes = [vp, C.c_int32, C.c_int32]
     lib.pb_fuse_frames_ws.restype = C.c_int
@@ -262,6 +265,14 @@ def pb_fuse_frames_select(tree: Tree, d_logp, frame_stride: int, row_stride: int
     _check(load().pb_fuse_frames_select(tree.handle, _dptr(d_logp), frame_stride, row_stride, _dptr(d_states0),
                                         _dptr(d_last0), alpha, T, B, mode, _dptr(d_tokens), _dptr(d_states),
                                         _dptr(d_scores), stream or None), "pb_fuse_frames_select")
+
+
+def pb_fuse_frames_plan(tree: Tree, T: int, B: int):
+    """Frame indices at which pb_fuse_frames* would cut a call: a list of n_segments + 1 boundaries (empty plan: [0])."""
+    n = C.c_int32(0)
+    bounds = (C.c_int32 * 65)()
+    _check(load().pb_fuse_frames_plan(tree.handle, T, B, C.byref(n), bounds), "pb_fuse_frames_plan")
+    return [int(bounds[j]) for j in range(n.value + 1)]
 
 
 def pb_fuse_frames_workspace_bytes(tree: Tree, T: int, B: int) -> int:

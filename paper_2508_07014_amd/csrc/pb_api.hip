@@ -266,6 +266,21 @@ int64_t pb_fuse_frames_workspace_bytes(const pb_tree* tree, int32_t T, int32_t B
   return pb::frames_workspace_bytes(shape, T, B);
 }
 
+int pb_fuse_frames_plan(const pb_tree* tree, int32_t T, int32_t B, int32_t* n_segments, int32_t* bounds) {
+  if (!tree || !n_segments || T < 0 || B < 0) return PB_EINVAL;
+  if (T == 0 || B == 0) {
+    *n_segments = 0;
+    if (bounds) bounds[0] = 0;
+    return PB_OK;
+  }
+  const bool wide = tree->host.vocab_size > 1024;  // (rows wider than a chunk aim for fewer, longer chains)
+  const pb::SegPlan plan = pb::plan_segments(T, B, wide ? pb::kWideTargetChains : pb::kTargetChains);
+  *n_segments = plan.nseg;
+  if (bounds)
+    for (int j = 0; j <= plan.nseg; ++j) bounds[j] = pb::seg_begin(j, T, plan.nseg);
+  return PB_OK;
+}
+
 int pb_fuse_frames_ws(const pb_tree* tree, const float* d_logp, int64_t frame_stride, int64_t row_stride,
                       const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B, int32_t mode,
                       int32_t* d_tokens, int32_t* d_states, float* d_scores, void* d_workspace, int64_t workspace_bytes,

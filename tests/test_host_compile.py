@@ -259,3 +259,34 @@ def test_host_compiler_is_clean_under_address_and_ub_sanitizers(tmp_path):
     run = subprocess.run([exe], capture_output=True, text=True)
     assert run.returncode == 0, run.stdout + run.stderr
     assert "clean" in run.stdout
+
+
+def test_segment_plan_covers_the_frames_evenly_with_a_mild_taper():
+    """Host side of the multi-frame decoder: how a call is cut into segments (pb_fuse_frames_plan).  Whatever the
+    shape, the segments must tile [0, T) without gaps, none may be empty, there are at most 64 per hypothesis, and
+    they are even up to the taper (first segments longer, last shorter, by about a twentieth of the mean)."""
+    narrow = pb.pb_build(np.array([1, 2, 3], np.int32), np.array([0, 3], np.int64), 64, 0, device=-1)
+    wide = pb.pb_build(np.array([1, 2, 3], np.int32), np.array([0, 3], np.int64), 4096, 0, device=-1)
+    try:
+        for tree, target in ((narrow, 4096), (wide, 2048)):
+            assert pb.pb_fuse_frames_plan(tree, 0, 5) == [0] and pb.pb_fuse_frames_plan(tree, 5, 0) == [0]
+            for T in list(range(1, 140)) + [255, 256, 257, 500, 1000, 1023, 4096, 10007]:
+                for B in (1, 2, 3, 7, 31, 64, 128, 256, 1000, 2048, 5000):
+                    b = pb.pb_fuse_frames_plan(tree, T, B)
+                    n = len(b) - 1
+                    assert 1 <= n <= 64 and b[0] == 0 and b[-1] == T, (T, B, b)
+                    lens = np.diff(b)
+                    assert lens.min() >= 1, (T, B, b)
+                    mean = T / n
+                    assert lens.max() <= mean * 1.05 + 2 and lens.min() >= mean * 0.95 - 2, (T, B, lens)
+                    if n >= 4 and mean >= 40:   # the taper: the first quarter is longer than the last
+                        q = n // 4
+                        assert lens[:q].mean() > lens[-q:].mean(), (T, B, lens)
+                    # enough chains to fill the chip when the call is long enough, never more than about twice the aim
+                    if T >= 8 * 64:
+                        assert n * B >= min(target, 64 * B) * 0.5, (T, B, n)
+        assert len(pb.pb_fuse_frames_plan(narrow, 1000, 128)) - 1 == 32
+        assert len(pb.pb_fuse_frames_plan(wide, 200, 256)) - 1 == 8
+    finally:
+        pb.pb_free(narrow)
+        pb.pb_free(wide)
