@@ -483,12 +483,9 @@ __device__ __forceinline__ bool run_frames_1k(const TreeView& t, const float* __
   Cursor cur = cursor_at(t, s);
   float c_p = cur.p_root;
   make_base_boost<SEL>(0, lane, t.blank, c_p, alpha, c, c);  // element-wise, in place
-  // Outputs.  The single-stage decode and every re-run keep those of up to 64 consecutive frames in the lanes
-  // and write them together, so that no store sits in the in-order queue of the loads; pass 1 of the two-stage
-  // rules, whose extra state would otherwise push registers to scratch memory, writes frame by frame.
-  constexpr bool DEFER = COMPARE || SEL == 0;
+  // Outputs: those of up to 64 consecutive frames are kept in the lanes and written together, so that no store
+  // sits in the in-order queue of the loads (measured on the two-stage rules: pass 1 of config 3 109 -> 102 us).
   LaneOut out{f0, 0, 0, 0.0f};
-  size_t o = static_cast<size_t>(f0) * B + b;
   bool row_in_lds = false;  // the LDS row holds the raw row of the frame decoded last
   // One frame with its row in ring slot U.  STEADY frames request the row NB-1 frames ahead without a
   // condition (the last frames of the range ask for the last row again): only then can the compiler
@@ -508,30 +505,21 @@ __device__ __forceinline__ bool run_frames_1k(const TreeView& t, const float* __
                         },
                         val, tok, row_in_lds);
     const int word = cur.s;
-    if (!DEFER) {
-      if (lane == 0) {
-        tokens[o] = tok;
-        states[o] = word;
-        scores[o] = val;
+    const int slot = f - out.base;
+    out.put(lane, f, tok, word, val);
+    if (COMPARE) {
+      // met the stored trajectory: this frame is written too (its score may differ), the rest stands
+      if (stored.state_at(slot) == word && (SEL != 2 || stored.token_at(slot) == tok)) {
+        out.template flush<true>(lane, slot + 1, B, b, tokens, states, scores);
+        PB_STAT(0, 1);
+        PB_STAT(1, f - f0 + 1);
+        return true;
       }
-      o += B;
-    } else {
-      const int slot = f - out.base;
-      out.put(lane, f, tok, word, val);
-      if (COMPARE) {
-        // met the stored trajectory: this frame is written too (its score may differ), the rest stands
-        if (stored.state_at(slot) == word && (SEL != 2 || stored.token_at(slot) == tok)) {
-          out.template flush<true>(lane, slot + 1, B, b, tokens, states, scores);
-          PB_STAT(0, 1);
-          PB_STAT(1, f - f0 + 1);
-          return true;
-        }
-      }
-      if (slot == 63 && f + 1 < f1) {  // (the last group is written at the end, after the boundary bit is known)
-        out.template flush<COMPARE>(lane, 64, B, b, tokens, states, scores);
-        out.base = f + 1;
-        if (COMPARE) stored.fetch(lane, f + 1, f1, B, b, tokens, states);
-      }
+    }
+    if (slot == 63 && f + 1 < f1) {  // (the last group is written at the end, after the boundary bit is known)
+      out.template flush<COMPARE>(lane, 64, B, b, tokens, states, scores);
+      out.base = f + 1;
+      if (COMPARE) stored.fetch(lane, f + 1, f1, B, b, tokens, states);
     }
     if (SEL == 2) last = tok;
     rp += frame_stride;
@@ -581,17 +569,11 @@ __device__ __forceinline__ bool run_frames_1k(const TreeView& t, const float* __
       }
       if (lane == 0) patch[0] = npatch;
     }
-    if (certified) {
-      if (DEFER) {
-        if (lane == f1 - 1 - out.base) out.st |= kGuessOk;
-      } else if (lane == 0) {
-        states[static_cast<size_t>(f1 - 1) * B + b] = cur.s | kGuessOk;
-      }
-    }
+    if (certified && lane == f1 - 1 - out.base) out.st |= kGuessOk;
   } else if (GUESS && patch != nullptr && f1 < T && lane == 0) {
     patch[0] = 0;
   }
-  if (DEFER) out.template flush<COMPARE>(lane, f1 - out.base, B, b, tokens, states, scores);
+  out.template flush<COMPARE>(lane, f1 - out.base, B, b, tokens, states, scores);
   if (COMPARE) {
     PB_STAT(0, 1);
     PB_STAT(1, f1 - f0);
