@@ -381,17 +381,22 @@ __device__ __forceinline__ void guess_boundary_1k(const TreeView& t, float (&x)[
 // decoded over the frames that follow, at most n_max of them, until they agree on state and label -- from there
 // on what the next range wrote is right.  The frames of track A up to that point go to `patch` (entry i in lane
 // i) and their number is returned; 0 if the tracks have not met.   rp: row of the first frame after the range.
+// Track A continues the caller's decode and uses its cache of base boosts (cA for c_pA, left in an unspecified
+// state; the caller's cursor is not used: after the last frame of a range it holds the state id only); track B
+// gets a cache of its own, so that two tracks whose states differ in their accumulated backoff do not rebuild one
+// cache twice per frame.
 template <bool FULL, int SEL>
 __device__ __forceinline__ int run_on_1k(const TreeView& t, const float* __restrict__ rp, int64_t frame_stride,
-                                         float alpha, int sA, int lastA, int sB, int lastB, int n_max,
-                                         int32_t* __restrict__ patch, float* row, unsigned* tags, int lane) {
+                                         float alpha, int sA, float (&cA)[16], float& c_pA, int lastA, int sB,
+                                         int lastB, int n_max, int32_t* __restrict__ patch, float* row, unsigned* tags,
+                                         int lane) {
   if (n_max <= 0 || !valid_state(t, sB)) return 0;
   const int V = t.V;
-  float x[16], xn[16], c[16];  // (one cache of base boosts for both tracks: it is rebuilt whenever p_root changes)
+  float x[16], xn[16], cB[16];
   load16<FULL>(rp, 0, V, lane, -INFINITY, x);
   Cursor ca = cursor_at(t, sA), cb = cursor_at(t, sB);
-  float c_p = ca.p_root;
-  rebuild_base_boost<FULL, SEL>(t, lane, c_p, alpha, c);
+  float c_pB = cb.p_root;
+  rebuild_base_boost<FULL, SEL>(t, lane, c_pB, alpha, cB);
   int e_tok = 0, e_st = 0;
   float e_sc = 0.0f;
   for (int i = 0; i < n_max; ++i) {
@@ -399,9 +404,9 @@ __device__ __forceinline__ int run_on_1k(const TreeView& t, const float* __restr
     int tokA, tokB;
     bool in_lds;
     const float* rpn = rp + static_cast<int64_t>(min(i + 1, n_max - 1)) * frame_stride;  // (the last frame asks for its own row again)
-    frame_1k<FULL, SEL, 1, 1, 4>(t, ca, x, c, c_p, alpha, row, tags, lane, lastA, true,
+    frame_1k<FULL, SEL, 1, 1, 4>(t, ca, x, cA, c_pA, alpha, row, tags, lane, lastA, true,
                                  [&]() { load16<FULL>(rpn, 0, V, lane, -INFINITY, xn); }, valA, tokA, in_lds);
-    frame_1k<FULL, SEL, 1, 1, 4>(t, cb, x, c, c_p, alpha, row, tags, lane, lastB, true, []() {}, valB, tokB, in_lds);
+    frame_1k<FULL, SEL, 1, 1, 4>(t, cb, x, cB, c_pB, alpha, row, tags, lane, lastB, true, []() {}, valB, tokB, in_lds);
     if (lane == i) {
       e_tok = tokA;
       e_st = ca.s;
@@ -563,8 +568,8 @@ __device__ __forceinline__ bool run_frames_1k(const TreeView& t, const float* __
       if (!certified) {
         // (at most up to the frame before the last one of the next range, whose state word carries that range's own bit)
         set_wave_priority(3);  // the kernel ends with these waves
-        npatch = run_on_1k<FULL, SEL>(t, rp, frame_stride, alpha, cur.s, last, g, glabel, min(kPatchMax, next_len - 1),
-                                      patch, row, tags, lane);
+        npatch = run_on_1k<FULL, SEL>(t, rp, frame_stride, alpha, cur.s, c, c_p, last, g, glabel,
+                                      min(kPatchMax, next_len - 1), patch, row, tags, lane);
         certified = npatch > 0;
       }
       if (lane == 0) patch[0] = npatch;
