@@ -207,9 +207,10 @@ int pb_fuse_frames_select(const pb_tree* tree, const float* d_logp, int64_t fram
  * pb_fuse_frames_ws -- pb_fuse_frames_select with a caller-owned workspace, the faster form of the same call
  * (identical outputs).  The decoder cuts the T frames of every hypothesis into segments decoded side by side,
  * each from a guess of the state the frame before it ends in; with the workspace a segment that finds the
- * guess for its right neighbour wrong repairs the neighbour's first frames itself and leaves them there, and
+ * guess for its right neighbour wrong repairs the neighbour's first frames itself and leaves them there
+ * (comparing with the first frames the neighbour has decoded, which every segment leaves there too), and
  * nothing is decoded a second time.
- *   d_workspace: device memory of at least pb_fuse_frames_workspace_bytes(tree, T, B) bytes, 4-byte aligned,
+ *   d_workspace: device memory of at least pb_fuse_frames_workspace_bytes(tree, T, B) bytes, 8-byte aligned,
  *   used only during the call (contents before and after mean nothing; two calls that overlap in time need
  *   two workspaces).  pb_fuse_frames_workspace_bytes returns the size (0 when the call needs none: T or B zero,
  *   or rows wider than 1024 tokens, which are repaired without it), or PB_EINVAL for a null tree or negative sizes.
@@ -233,13 +234,13 @@ int pb_fuse_frames_plan(const pb_tree* tree, int32_t T, int32_t B, int32_t* n_se
 /*
  * pb_fuse_frames_static -- pb_fuse_frames_ws for callers that cannot allocate device memory (code under HIP
  * graph capture, tight serving loops, harnesses that forbid allocation): the workspace is a fixed array inside
- * the library, 1 MiB per GPU, held from the first pb_build on that GPU until the process ends.  The call
+ * the library, 2 MiB per GPU, held from the first pb_build on that GPU until the process ends.  The call
  * allocates and frees nothing.  Outputs are those of pb_fuse_frames_ws.
- *   PB_EUNSUPPORTED when pb_fuse_frames_workspace_bytes(tree, T, B) exceeds 1 MiB (208 bytes per segment
- *   boundary; the library's segment plan keeps a call below 4096 boundaries = 832 KiB, so only a build with a
- *   larger plan can exceed it).  Nothing in the array has to be cleared between calls (every call writes all it
- *   reads), but every call on a GPU shares that GPU's array: two calls that overlap in time on one GPU, on any
- *   streams, race and may both return wrong results.
+ *   PB_EUNSUPPORTED when pb_fuse_frames_workspace_bytes(tree, T, B) exceeds 2 MiB (464 bytes per segment
+ *   boundary; the library's segment plan keeps a call below 4096 boundaries = 1856 KiB, so only a build with a
+ *   larger plan can exceed it).  Nothing in the array has to be cleared between calls (a call reads only what it
+ *   has written itself), but every call on a GPU shares that GPU's array: two calls that overlap in time on one
+ *   GPU, on any streams, race and may both return wrong results.
  */
 int pb_fuse_frames_static(const pb_tree* tree, const float* d_logp, int64_t frame_stride, int64_t row_stride,
                           const int32_t* d_states0, const int32_t* d_last0, float alpha, int32_t T, int32_t B,

@@ -21,7 +21,7 @@ constexpr size_t kAlign = 256;
 // callers that cannot allocate.  Every GPU the library runs on holds its own copy until the process ends.  In
 // host code the array's name is only a stand-in for the symbol: its device address is looked up once per device
 // (with that device current) and that address is what the launches get.
-constexpr int64_t kStaticScratchBytes = 1ll << 20;
+constexpr int64_t kStaticScratchBytes = 2ll << 20;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 constexpr int kMaxDevices = 64;
 void* g_scratch_ptr[kMaxDevices] = {};
@@ -287,7 +287,7 @@ int pb_fuse_frames_ws(const pb_tree* tree, const float* d_logp, int64_t frame_st
                       void* hip_stream) {
   if (!on_device(tree) || B < 0 || T < 0 || workspace_bytes < 0) return PB_EINVAL;
   const int64_t need = (T == 0 || B == 0) ? 0 : pb::frames_workspace_bytes(tree->dev, T, B);
-  if (need > 0 && (!d_workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(d_workspace) & 3u) != 0))
+  if (need > 0 && (!d_workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(d_workspace) & 7u) != 0))
     return PB_EINVAL;
   return fuse_frames_any(tree, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B, mode, d_tokens, d_states,
                          d_scores, need > 0 ? static_cast<int32_t*>(d_workspace) : nullptr, hip_stream);

@@ -37,9 +37,12 @@
 //    ever selects.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+#include <chrono>
 #include <climits>
 #include <cmath>
 #include <cstdint>
+#include <random>
 #include <type_traits>
 
 #include "pb_kernels.hpp"
@@ -376,45 +379,57 @@ __device__ __forceinline__ void guess_boundary_1k(const TreeView& t, float (&x)[
   }
 }
 
-// A wrong boundary guess, repaired where it is found.  Track A starts from the real outcome (state sA, label
-// lastA) at the end of a range, track B from the guess (sB, lastB) the next range was decoded from; both are
-// decoded over the frames that follow, at most n_max of them, until they agree on state and label -- from there
-// on what the next range wrote is right.  The frames of track A up to that point go to `patch` (entry i in lane
-// i) and their number is returned; 0 if the tracks have not met.   rp: row of the first frame after the range.
-// Track A continues the caller's decode and uses its cache of base boosts (cA for c_pA, left in an unspecified
-// state; the caller's cursor is not used: after the last frame of a range it holds the state id only); track B
-// gets a cache of its own, so that two tracks whose states differ in their accumulated backoff do not rebuild one
-// cache twice per frame.
+// A wrong boundary guess, repaired where it is found.  The range that ends here decodes on from its real outcome
+// (state sA, label lastA) over the frames that follow, at most n_max of them, until it agrees on state and label
+// with the trajectory the guess has led to -- from there on what the next range wrote is right.  That trajectory
+// is read from the start record the next range leaves as it goes (`start_rec`, its tag in tag_lo / tag_hi; see
+// kStartInts), so only one track is decoded.  The frames decoded up to the meeting point go to `patch` (entry i
+// in lane i) and their number is returned; 0 if the two have not met within n_max frames or a frame of the record
+// is not there (looked at twice): the boundary then stays uncertified and pass 2 decodes the next range again.
+// rp: row of the first frame after the range.  Uses the caller's cache of base boosts (c for c_p, left in an
+// unspecified state; the caller's cursor is not used: after the last frame of a range it holds the state id only).
 template <bool FULL, int SEL>
 __device__ __forceinline__ int run_on_1k(const TreeView& t, const float* __restrict__ rp, int64_t frame_stride,
-                                         float alpha, int sA, float (&cA)[16], float& c_pA, int lastA, int sB,
-                                         int lastB, int n_max, int32_t* __restrict__ patch, float* row, unsigned* tags,
-                                         int lane) {
-  if (n_max <= 0 || !valid_state(t, sB)) return 0;
+                                         float alpha, int sA, float (&c)[16], float& c_p, int lastA, int n_max,
+                                         int32_t* __restrict__ patch, float* row, unsigned* tags, int lane,
+                                         const int32_t* start_rec, unsigned tag_lo) {
+  if (n_max <= 0 || start_rec == nullptr) return 0;
+  const unsigned tag_hi = start_tag_hi(tag_lo);
   const int V = t.V;
-  float x[16], xn[16], cB[16];
+  int b_st = 0, b_tok = 0;  // lane i: state and token of the guessed trajectory after frame i
+  const bool b_mine = read_start_frame(start_rec, min(lane, kPatchMax - 1), tag_lo, tag_hi, b_st, b_tok);
+  u64 there = __ballot(b_mine);
+  float x[16], xn[16];
   load16<FULL>(rp, 0, V, lane, -INFINITY, x);
-  Cursor ca = cursor_at(t, sA), cb = cursor_at(t, sB);
-  float c_pB = cb.p_root;
-  rebuild_base_boost<FULL, SEL>(t, lane, c_pB, alpha, cB);
+  Cursor ca = cursor_at(t, sA);
   int e_tok = 0, e_st = 0;
   float e_sc = 0.0f;
   for (int i = 0; i < n_max; ++i) {
-    float valA, valB;
-    int tokA, tokB;
+    float valA;
+    int tokA;
     bool in_lds;
     const float* rpn = rp + static_cast<int64_t>(min(i + 1, n_max - 1)) * frame_stride;  // (the last frame asks for its own row again)
-    frame_1k<FULL, SEL, 1, 1, 4>(t, ca, x, cA, c_pA, alpha, row, tags, lane, lastA, true,
+    frame_1k<FULL, SEL, 1, 1, 4>(t, ca, x, c, c_p, alpha, row, tags, lane, lastA, true,
                                  [&]() { load16<FULL>(rpn, 0, V, lane, -INFINITY, xn); }, valA, tokA, in_lds);
-    frame_1k<FULL, SEL, 1, 1, 4>(t, cb, x, cB, c_pB, alpha, row, tags, lane, lastB, true, []() {}, valB, tokB, in_lds);
+    if (((there >> i) & 1ull) == 0) {  // not there when first looked at: look once more
+      int st1, tok1;
+      const bool now = read_start_frame(start_rec, i, tag_lo, tag_hi, st1, tok1);
+      st1 = uniform_i(st1);  // (every lane has read the same two words)
+      tok1 = uniform_i(tok1);
+      if (uniform_i(now ? 1 : 0) == 0) return 0;
+      if (lane == i) {
+        b_st = st1;
+        b_tok = tok1;
+      }
+    }
+    const int stB = plain_state(__builtin_amdgcn_readlane(b_st, i)), tokB = __builtin_amdgcn_readlane(b_tok, i);
     if (lane == i) {
       e_tok = tokA;
       e_st = ca.s;
       e_sc = valA;
     }
     lastA = tokA;
-    lastB = tokB;
-    if (ca.s == cb.s && (SEL != 2 || tokA == tokB)) {
+    if (ca.s == stB && (SEL != 2 || tokA == tokB)) {
       if (lane <= i) {
         patch[4 + lane] = e_tok;
         patch[4 + kPatchMax + lane] = e_st;
@@ -445,7 +460,8 @@ __device__ __forceinline__ bool run_frames_1k(const TreeView& t, const float* __
                                               int last_in, int T, const int32_t* __restrict__ states0,
                                               int32_t* __restrict__ patch, int next_len,
                                               int32_t* __restrict__ tokens, int32_t* __restrict__ states,
-                                              float* __restrict__ scores, float* row, unsigned* tags, int lane) {
+                                              float* __restrict__ scores, float* row, unsigned* tags, int lane,
+                                              int32_t* start_rec = nullptr, unsigned tag_lo = 0u) {
   if (f0 >= f1) return true;
   constexpr bool GUESS = EDGE && !COMPARE;
   const int V = t.V;
@@ -491,6 +507,10 @@ __device__ __forceinline__ bool run_frames_1k(const TreeView& t, const float* __
   // Outputs: those of up to 64 consecutive frames are kept in the lanes and written together, so that no store
   // sits in the in-order queue of the loads (measured on the two-stage rules: pass 1 of config 3 109 -> 102 us).
   LaneOut out{f0, 0, 0, 0.0f};
+  // (the repair of a boundary looks at up to kPatchMax frames of the range behind it, never at its last one)
+  // `start_rec`: the start record of the boundary behind this range (read by its repair); the record of the
+  // boundary before it, which this range fills, lies B records earlier.
+  const int pub_frame = (GUESS && start_rec != nullptr && f0 > 0 && f1 - f0 >= 2) ? f0 + min(kPatchMax, f1 - f0 - 1) - 1 : -1;
   bool row_in_lds = false;  // the LDS row holds the raw row of the frame decoded last
   // One frame with its row in ring slot U.  STEADY frames request the row NB-1 frames ahead without a
   // condition (the last frames of the range ask for the last row again): only then can the compiler
@@ -512,6 +532,12 @@ __device__ __forceinline__ bool run_frames_1k(const TreeView& t, const float* __
     const int word = cur.s;
     const int slot = f - out.base;
     out.put(lane, f, tok, word, val);
+    // The first frames of the range, for whoever repairs the boundary before it.  A store sits in the in-order
+    // queue of the loads, so they go out in two groups: frames 0-5 (a range that is slow there, in deep states,
+    // would otherwise have nothing to show when its neighbour asks) and the rest.
+    if (GUESS && f <= pub_frame && (slot == 5 || f == pub_frame))
+      publish_start_frames(start_rec - static_cast<size_t>(B) * kStartInts, lane, slot <= 5 ? 0 : 6, slot, out.st, out.tok,
+                           tag_lo, start_tag_hi(tag_lo));
     if (COMPARE) {
       // met the stored trajectory: this frame is written too (its score may differ), the rest stands
       if (stored.state_at(slot) == word && (SEL != 2 || stored.token_at(slot) == tok)) {
@@ -568,8 +594,8 @@ __device__ __forceinline__ bool run_frames_1k(const TreeView& t, const float* __
       if (!certified) {
         // (at most up to the frame before the last one of the next range, whose state word carries that range's own bit)
         set_wave_priority(3);  // the kernel ends with these waves
-        npatch = run_on_1k<FULL, SEL>(t, rp, frame_stride, alpha, cur.s, c, c_p, last, g, glabel,
-                                      min(kPatchMax, next_len - 1), patch, row, tags, lane);
+        npatch = run_on_1k<FULL, SEL>(t, rp, frame_stride, alpha, cur.s, c, c_p, last, min(kPatchMax, next_len - 1),
+                                      patch, row, tags, lane, f1 < T ? start_rec : nullptr, tag_lo);
         certified = npatch > 0;
       }
       if (lane == 0) patch[0] = npatch;
@@ -599,7 +625,7 @@ __global__ void __launch_bounds__(256, 4) frames_spec_kernel(DeviceTree dt, Tree
                                                           const int32_t* __restrict__ states0,
                                                           const int32_t* __restrict__ last0, float alpha, int T, int B,
                                                           int seg_len, int nseg, int32_t* __restrict__ patches,
-                                                          int32_t* __restrict__ tokens,
+                                                          unsigned tag_lo, int32_t* __restrict__ tokens,
                                                           int32_t* __restrict__ states, float* __restrict__ scores) {
   extern __shared__ float lds[];
   const int lane = threadIdx.x & 63, wave = uniform_i(threadIdx.x >> 6);
@@ -621,9 +647,12 @@ __global__ void __launch_bounds__(256, 4) frames_spec_kernel(DeviceTree dt, Tree
   if (!tree_ok) s = -1;  // an unknown tree marks every frame of the hypothesis like an invalid state
   int32_t* patch = nullptr;  // the record of the boundary after this segment
   if (patches != nullptr && f1 < T) patch = patches + (static_cast<size_t>(j) * B + b) * kPatchInts;
+  // start records, behind the patches: that of the boundary behind this segment (the one it fills lies B earlier)
+  int32_t* start_recs = patches != nullptr ? patches + static_cast<size_t>(nseg - 1) * B * kPatchInts : nullptr;
+  int32_t* start_rec = start_recs != nullptr ? start_recs + (static_cast<size_t>(j) * B + b) * kStartInts : nullptr;
   run_frames_1k<false, FULL, SEL, true>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, T, states0,
                                         patch, (j + 2 <= nseg ? seg_begin(j + 2, T, nseg) : f1) - f1, tokens, states, scores,
-                                        row, tags, lane);
+                                        row, tags, lane, start_rec, tag_lo);
 }
 
 // Pass 2: one workgroup per hypothesis; its waves share the segments j = 1 .. nseg-1.
@@ -923,10 +952,20 @@ int launch_step_wave(const DeviceTree& t, const TreePick& pick, const float* d_l
   return hipGetLastError() == hipSuccess ? PB_OK : PB_EHIP;
 }
 
+// A number that no earlier call of this process has used: a counter from a random 64-bit start.
+uint64_t next_call_tag() {
+  static std::atomic<uint64_t> counter{[] {
+    std::random_device rd;
+    const uint64_t a = rd(), b = rd();
+    return (a << 32) ^ b ^ static_cast<uint64_t>(std::chrono::steady_clock::now().time_since_epoch().count());
+  }()};
+  return counter.fetch_add(0x9E3779B97F4A7C15ull, std::memory_order_relaxed);  // (odd step: all 2^64 values in turn)
+}
+
 int64_t frames_workspace_bytes(const DeviceTree& t, int32_t T, int32_t B) {
   if (t.vocab_size > kChunk) return 0;  // (wide rows repair wrong guesses in pass 2)
   const SegPlan plan = plan_segments(T, B, kTargetChains);
-  return static_cast<int64_t>(plan.nseg - 1) * B * kPatchInts * static_cast<int64_t>(sizeof(int32_t));
+  return static_cast<int64_t>(plan.nseg - 1) * B * (kPatchInts + kStartInts) * static_cast<int64_t>(sizeof(int32_t));
 }
 
 int launch_frames_wave(const DeviceTree& t, const TreePick& pick, const float* d_logp, int64_t frame_stride,
@@ -939,6 +978,8 @@ int launch_frames_wave(const DeviceTree& t, const TreePick& pick, const float* d
   const SegPlan plan = plan_segments(T, B, kTargetChains);
   const int nseg = plan.nseg, seg_len = plan.seg_len;
   const int64_t chains = static_cast<int64_t>(B) * nseg;
+  const uint64_t tag = next_call_tag();  // marks the start records of this call (see kStartInts)
+  const unsigned tag_lo = static_cast<unsigned>(tag);
   const int waves = 4;
   const int64_t blocks = (chains + waves - 1) / waves;
   if (blocks > INT32_MAX) return PB_EUNSUPPORTED;
@@ -948,7 +989,7 @@ int launch_frames_wave(const DeviceTree& t, const TreePick& pick, const float* d
 #define PB_SPEC(FULL, SEL, FOREST)                                                                                   \
   hipLaunchKernelGGL((frames_spec_kernel<FULL, SEL, FOREST>), dim3(static_cast<unsigned>(blocks)), dim3(64 * waves), \
                      lds, stream, t, pick, d_logp, frame_stride, row_stride, d_states0, d_last0, alpha, T, B,        \
-                     seg_len, nseg, d_patches, d_tokens, d_states, d_scores)
+                     seg_len, nseg, d_patches, tag_lo, d_tokens, d_states, d_scores)
 #define PB_LAUNCH(FULL, SEL) PB_SPEC(FULL, SEL, false)
 #define PB_LAUNCH_F(FULL, SEL) PB_SPEC(FULL, SEL, true)
   if (forest) {

@@ -283,6 +283,23 @@ constexpr int kLookBack = 8;
 constexpr int kPatchMax = 16;
 constexpr int kPatchInts = 4 + 3 * kPatchMax;
 
+// Start records (same workspace, behind the patches).  The repair above needs the trajectory the guess leads to,
+// and the segment on the right decodes exactly that: it leaves the states and tokens of its first frames in the
+// record of its left boundary (in two groups: a store sits in the in-order queue of the loads).  The segment on the left, when it comes to repair that boundary
+// (usually tens of microseconds later), reads the record instead of decoding the guessed trajectory a second
+// time; from the first frame that is not there (yet) it decodes both, as before.
+//   No fence orders these accesses (a release at agent scope writes back the whole L2 of the XCD: with one per
+//   segment pass 1 took 283 us instead of 102).  Instead every 64-bit word of a record validates itself: its upper
+//   half is one half of a 64-bit tag of the call (the host draws 32 bits of it, a counter from a random start, the
+//   other 32 are a fixed function of those; no two of 2^32 consecutive calls share a tag), its lower half
+//   the state or the token, written and read with one relaxed atomic access each (at system scope: the writer and
+//   the reader sit on different XCDs, and at agent scope a few reads in a thousand still found an old copy).  A word shows the
+//   tag only if this call has written it, up to a memory that happens to hold the tag already: 2^-64 per frame.
+// One record per boundary: kPatchMax pairs of words, (tag_lo : state) and (tag_hi : token).
+constexpr int kStartInts = 4 * kPatchMax;
+// The upper half of a call's tag from its lower half (the host draws the lower half: a counter from a random start).
+__device__ __forceinline__ unsigned start_tag_hi(unsigned tag_lo) { return (tag_lo * 0x9E3779B1u) ^ 0x85EBCA6Bu; }
+
 // Issue priority of the wave (0..3, wave-uniform).  The waves of pass 1 all have the same amount of work, but a
 // SIMD serves its oldest wave first: measured with time stamps, the waves launched first ended at 73 us and those
 // launched last at 96 us of a 107 us kernel, which then drains with a long, thin tail.  A wave's priority falls
@@ -322,6 +339,30 @@ __device__ __forceinline__ void fill_invalid(int B, int b, int f0, int f1, int32
     publish_i32(states + o, -1);
     scores[o] = NAN;
   }
+}
+
+// Publishes frames lo..hi of a range (lane l holds the state and token of frame l) in the start record `rec`
+// (8-byte aligned), see kStartInts.  Called by all lanes.
+__device__ __forceinline__ void publish_start_frames(int32_t* rec, int lane, int lo, int hi, int st, int tok,
+                                                     unsigned tag_lo, unsigned tag_hi) {
+  if (lane >= lo && lane <= hi) {
+    u64* w = reinterpret_cast<u64*>(rec) + 2 * lane;
+    __hip_atomic_store(w, (static_cast<u64>(tag_lo) << 32) | static_cast<unsigned>(st), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_SYSTEM);
+    __hip_atomic_store(w + 1, (static_cast<u64>(tag_hi) << 32) | static_cast<unsigned>(tok), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_SYSTEM);
+  }
+}
+// Reads frame i of the start record `rec` (i < kPatchMax; any lane may ask for any frame).  Returns whether this
+// call has written it; st / tok are then its state and token.
+__device__ __forceinline__ bool read_start_frame(const int32_t* rec, int i, unsigned tag_lo, unsigned tag_hi, int& st,
+                                                 int& tok) {
+  const u64* w = reinterpret_cast<const u64*>(rec) + 2 * i;
+  const u64 a = __hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  const u64 b = __hip_atomic_load(w + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  st = static_cast<int>(static_cast<unsigned>(a));
+  tok = static_cast<int>(static_cast<unsigned>(b));
+  return static_cast<unsigned>(a >> 32) == tag_lo && static_cast<unsigned>(b >> 32) == tag_hi;
 }
 
 // Outputs of up to 64 consecutive frames held one per lane (frame base + l in lane l) and written
