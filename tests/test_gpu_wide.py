@@ -177,6 +177,33 @@ def test_frames_with_workspace_config3_planted_and_blank_heavy():
                              500, B, 0, ws, ws, ws, ws, need - 4, 0)
 
 
+def test_workspace_reused_back_to_back_with_other_inputs():
+    """One workspace, calls on different inputs queued one behind the other without a synchronisation in between:
+    what an earlier call has left in the workspace (patches, the first frames of every segment) must mean nothing
+    to the next one.  Planted rows first (many repairs), then other rows of the same shape, then a shorter call."""
+    cfg, toks, offs, ot, tr = config_trees(3)
+    B, V, T = cfg.batch, cfg.vocab_size, 400
+    inputs = [W.make_logp(cfg, steps=T, seed=11, planting=W.Planting(toks, offs)),
+              W.make_logp(cfg, steps=T, seed=12, planting=W.Planting(toks, offs)),
+              W.make_logp(cfg, steps=T, seed=13, blank_bias=8.0, blank_frac=0.75),
+              W.make_logp(cfg, steps=173, seed=14, planting=W.Planting(toks, offs))]
+    need = max(pb.pb_fuse_frames_workspace_bytes(tr, x.shape[0], B) for x in inputs)
+    ws = torch.full((need // 4,), -1, dtype=torch.int32, device=DEV)   # (never cleared)
+    s0 = dev(np.zeros(B, np.int32))
+    for mode in (0, 2):
+        d_in = [dev(x) for x in inputs]
+        outs = [(torch.full(x.shape[:2], -7, dtype=torch.int32, device=DEV), torch.full(x.shape[:2], -7, dtype=torch.int32, device=DEV),
+                 torch.zeros(x.shape[:2], dtype=torch.float32, device=DEV)) for x in inputs]
+        for rep in range(2):
+            for x, d, o in zip(inputs, d_in, outs):
+                pb.pb_fuse_frames_ws(tr, d, B * V, V, s0, None, cfg.alpha, x.shape[0], B, mode, o[0], o[1], o[2], ws, need, 0)
+        torch.cuda.synchronize()
+        for k, (x, o) in enumerate(zip(inputs, outs)):
+            want = ot.fuse_frames_select(x, np.zeros(B, np.int32), None, cfg.alpha, mode)
+            for g, w in zip(o, want):
+                assert np.array_equal(g.cpu().numpy(), w), (mode, k)
+
+
 def _chain_steps(tr, logp, alpha, mode=0):
     """T calls of the step entry point, each fed with the states (and labels) the previous call left on the GPU."""
     T, B, V = logp.shape
