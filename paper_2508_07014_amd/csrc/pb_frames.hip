@@ -30,7 +30,9 @@
 //    trajectory.  The segment on the left certifies a right guess with a bit in its last state word;
 //    a second kernel re-runs the other segments (in parallel, from the neighbouring segment's end
 //    state), then compares the assumed start states with the final ones, re-running stale segments in
-//    parallel rounds, and clears the bits.  The result is identical to T sequential steps.
+//    parallel rounds, and clears the bits.  With a workspace the segment on the left repairs a wrong guess
+//    itself (it decodes on until it meets what the segment on the right has left of its first frames) and
+//    the second kernel only copies the repaired frames.  The result is identical to T sequential steps.
 //  * Selection rules (Sec. II-C).  The two-stage rules first take the arg-max of the raw row; a blank
 //    (or, for CTC, a repeat of the previous label) ends the frame there.  Tokens barred from the
 //    boosted re-selection are NaN in the candidate registers, which no maximum and no equality test

@@ -276,25 +276,26 @@ constexpr int kGuessOk = 1 << 30;
 constexpr int kLookBack = 8;
 
 // Patches (optional workspace of the multi-frame decoder).  A segment that finds its guess for the next segment
-// wrong decodes on from its real outcome, next to the trajectory the guess leads to, until the two meet -- at
-// most kPatchMax frames, usually one to three -- and leaves the frames it has decoded as a patch for the start
-// of the next segment.  The boundary then counts as certified, and pass 2 only copies the patch over what the
-// next segment wrote; nothing is decoded again.  One record per boundary: count, then tokens, states, scores.
+// wrong decodes on from its real outcome until it meets the trajectory the guess has led to -- at most kPatchMax
+// frames, usually one to three -- and leaves the frames it has decoded as a patch for the start of the next
+// segment.  The boundary then counts as certified, and pass 2 only copies the patch over what the next segment
+// wrote; nothing is decoded again.  One record per boundary: count, then tokens, states, scores.
 constexpr int kPatchMax = 16;
 constexpr int kPatchInts = 4 + 3 * kPatchMax;
 
-// Start records (same workspace, behind the patches).  The repair above needs the trajectory the guess leads to,
-// and the segment on the right decodes exactly that: it leaves the states and tokens of its first frames in the
-// record of its left boundary (in two groups: a store sits in the in-order queue of the loads).  The segment on the left, when it comes to repair that boundary
-// (usually tens of microseconds later), reads the record instead of decoding the guessed trajectory a second
-// time; from the first frame that is not there (yet) it decodes both, as before.
+// Start records (same workspace, behind the patches).  The repair above needs the trajectory the guess has led
+// to, and the segment on the right decodes exactly that: it leaves the states and tokens of its first frames in
+// the record of its left boundary (in two groups: a store sits in the in-order queue of the loads).  The segment
+// on the left, when it comes to repair that boundary (usually tens of microseconds later), reads them there; a
+// frame that is not there (looked at twice) ends the repair, and pass 2 decodes the segment on the right again.
 //   No fence orders these accesses (a release at agent scope writes back the whole L2 of the XCD: with one per
-//   segment pass 1 took 283 us instead of 102).  Instead every 64-bit word of a record validates itself: its upper
-//   half is one half of a 64-bit tag of the call (the host draws 32 bits of it, a counter from a random start, the
-//   other 32 are a fixed function of those; no two of 2^32 consecutive calls share a tag), its lower half
-//   the state or the token, written and read with one relaxed atomic access each (at system scope: the writer and
-//   the reader sit on different XCDs, and at agent scope a few reads in a thousand still found an old copy).  A word shows the
-//   tag only if this call has written it, up to a memory that happens to hold the tag already: 2^-64 per frame.
+//   segment pass 1 took 283 us instead of 102).  Instead every 64-bit word of a record validates itself: its
+//   upper half is one half of a 64-bit tag of the call (the host draws 32 bits of it, a counter from a random
+//   start, the other 32 are a fixed function of those; no two of 2^32 consecutive calls share a tag), its lower
+//   half the state or the token, written and read with one relaxed atomic access each (at system scope: the
+//   writer and the reader sit on different XCDs, and at agent scope a few reads in a thousand still found an old
+//   copy).  A word shows the tag only if this call has written it, up to memory that happens to hold the tag
+//   already: 2^-64 per frame.
 // One record per boundary: kPatchMax pairs of words, (tag_lo : state) and (tag_hi : token).
 constexpr int kStartInts = 4 * kPatchMax;
 // The upper half of a call's tag from its lower half (the host draws the lower half: a counter from a random start).
