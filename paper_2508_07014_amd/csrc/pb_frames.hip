@@ -16,8 +16,9 @@
 //    with ballots over the four 256-token groups.
 //  * Arc candidates.  The failure chain is walked with scalar loads (the state is wave-uniform);
 //    at each chain state the lanes take one arc each, gather its log-prob from the LDS copy of the
-//    row and evaluate Eq. 1 for it.  Chains with more than one state mark each token in an LDS bit
-//    set so that an arc shadowed by a deeper chain state is skipped.  If the base winner is itself an
+//    row and evaluate Eq. 1 for it.  In a chain with more than one state an evaluated arc leaves a NaN
+//    in its token's entry of that copy (the CTC rule: a mark in an LDS bit set), so that an arc shadowed
+//    by a deeper chain state is skipped.  If the base winner is itself an
 //    overridden token and the arcs do not beat it, a second pass recomputes the base winner
 //    without the overridden tokens.
 //  * The record of the next state (arc range, failure link, backoffs) is fetched with the lookup
@@ -139,7 +140,8 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
     for (int j = 0; j < 16; ++j) f[j] = slot_is(j, ln, t.eos) ? __fadd_rn(x[j], ce) : f[j];
   }
   if (chain) store_row_lds(row, lane, x);
-  row_in_lds = chain;
+  constexpr bool MARK_IN_ROW = SEL != 2;  // how an arc finds its token claimed by a deeper chain state, see below
+  row_in_lds = chain && !(MARK_IN_ROW && multi);  // (such a chain leaves marks in the copy)
   const Cursor start = cur;
   // The CTC rule bars the previous label from the re-selection.  The frame is first decided with the
   // label still in; only if it wins is the frame decided again with the label excluded (excl >= 0).
@@ -165,18 +167,26 @@ __device__ __forceinline__ void frame_1k(const TreeView& t, Cursor& cur, const f
     int btok = INT_MAX, bchild = 0;
     bool hit_vb = false;
     if (chain) {
-      if (multi) tags_clear(tags, lane);
-      // one arc per lane: `a` with its child state, on chain level `level` with accumulated backoff p
+      // One arc per lane: `a` with its child state, on chain level `level` with accumulated backoff p.  A chain
+      // of several states is walked deepest state first, and an arc whose token a deeper state has already
+      // claimed must be skipped: every arc that is evaluated replaces its token's entry in the LDS copy of the
+      // row by a NaN, so a later arc on the same token computes a NaN, which no comparison selects.  (The
+      // tokens of one state are distinct, and LDS accesses of a wave complete in order.)  The CTC rule may decide
+      // a frame twice and would need the row again for that, which the registers of its kernels do not hold:
+      // it marks the claimed tokens in a bit set beside the row instead (one more LDS round trip per batch).
+      if (!MARK_IN_ROW && multi) tags_clear(tags, lane);
       auto eval = [&](const ArcRec& a, bool valid, int child, float p, int level) {
         const int tk = valid ? a.token : 0;  // an unused entry may hold anything: keep the LDS index in range
         bool shadowed = !valid;
         if (SEL == 2) shadowed = shadowed || tk == excl;
-        if (multi) {
-          if (level > 0) shadowed = shadowed || tag_test(tags, tk);  // a deeper chain state owns this token
+        if (!MARK_IN_ROW && multi) {
+          if (level > 0) shadowed = shadowed || tag_test(tags, tk);
           if (valid) tag_set(tags, tk);
         }
+        const float lp = row[tk];
+        if (MARK_IN_ROW && multi && valid) row[tk] = NAN;
         hit_vb = hit_vb || (valid && tk == vb);
-        const float fa = __fadd_rn(row[tk], __fmul_rn(alpha, __fadd_rn(p, a.score)));
+        const float fa = __fadd_rn(lp, __fmul_rn(alpha, __fadd_rn(p, a.score)));
         const bool take = !shadowed & ((fa > bf) | ((fa == bf) & (tk < btok)));  // (no short-circuit: no branches)
         bf = take ? fa : bf;
         btok = take ? tk : btok;
@@ -398,12 +408,12 @@ __device__ __forceinline__ int run_on_1k(const TreeView& t, const float* __restr
   if (n_max <= 0 || start_rec == nullptr) return 0;
   const unsigned tag_hi = start_tag_hi(tag_lo);
   const int V = t.V;
+  float x[16], xn[16];
+  load16<FULL>(rp, 0, V, lane, -INFINITY, x);  // (requested before the record is waited for)
+  Cursor ca = cursor_at(t, sA);
   int b_st = 0, b_tok = 0;  // lane i: state and token of the guessed trajectory after frame i
   const bool b_mine = read_start_frame(start_rec, min(lane, kPatchMax - 1), tag_lo, tag_hi, b_st, b_tok);
   u64 there = __ballot(b_mine);
-  float x[16], xn[16];
-  load16<FULL>(rp, 0, V, lane, -INFINITY, x);
-  Cursor ca = cursor_at(t, sA);
   int e_tok = 0, e_st = 0;
   float e_sc = 0.0f;
   for (int i = 0; i < n_max; ++i) {
