@@ -659,7 +659,8 @@ __global__ void __launch_bounds__(256, 4) frames_spec_kernel(DeviceTree dt, Tree
   if (!tree_ok) s = -1;  // an unknown tree marks every frame of the hypothesis like an invalid state
   int32_t* patch = nullptr;  // the record of the boundary after this segment
   if (patches != nullptr && f1 < T) patch = patches + (static_cast<size_t>(j) * B + b) * kPatchInts;
-  // start records, behind the patches: that of the boundary behind this segment (the one it fills lies B earlier)
+  // start records, behind the patches: that of the boundary behind this segment (the one it fills lies B earlier;
+  // for the last segment this address lies behind the records and is only used to find the one B earlier)
   int32_t* start_recs = patches != nullptr ? patches + static_cast<size_t>(nseg - 1) * B * kPatchInts : nullptr;
   int32_t* start_rec = start_recs != nullptr ? start_recs + (static_cast<size_t>(j) * B + b) * kStartInts : nullptr;
   run_frames_1k<false, FULL, SEL, true>(t, logp, frame_stride, row_stride, alpha, B, b, f0, f1, s, last, T, states0,
