@@ -37,9 +37,10 @@ constexpr int kMaxSegments = 64;     // segments per hypothesis (one lane each i
 
 constexpr int kWideMaxV = 16384;     // widest row of the wave kernels (the root scores of a row live in LDS)
 #ifndef PB_WIDE_TARGET_CHAINS
-#define PB_WIDE_TARGET_CHAINS 2048
+#define PB_WIDE_TARGET_CHAINS 1024
 #endif
-constexpr int kWideTargetChains = PB_WIDE_TARGET_CHAINS;  // the same for rows wider than 1024 tokens
+constexpr int kWideTargetChains = PB_WIDE_TARGET_CHAINS;  // the same for rows wider than 1024 tokens (one wave per SIMD:
+                                                          // a wave keeps three 4-KiB chunks of its rows in flight)
 
 struct SegPlan {
   int nseg, seg_len;  // segments per hypothesis and their nominal length
