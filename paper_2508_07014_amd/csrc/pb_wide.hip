@@ -34,7 +34,13 @@ namespace {
 
 using namespace wv;
 
-constexpr int kRing = 4;  // chunks in flight or in use per wave
+#ifndef PB_WIDE_RING
+#define PB_WIDE_RING 4
+#endif
+#ifndef PB_WIDE_WAVES_EU
+#define PB_WIDE_WAVES_EU 2
+#endif
+constexpr int kRing = PB_WIDE_RING;  // chunks in flight or in use per wave
 
 // Running arg-max of a lane over its tokens of a row; code = 16 * chunk + slot of the lane's token.
 struct LaneBest {
@@ -564,7 +570,7 @@ __device__ __forceinline__ void stage_root_scores(const TreeView& t, float* rs, 
 // Pass 1 (see frames_spec_kernel of the narrow rows).  With a table of trees the workgroup's waves may use
 // different trees, so each wave then keeps its own copy of the root scores.
 template <bool FULL, int SEL, bool FOREST>
-__global__ void __launch_bounds__(256, 2) wide_spec_kernel(DeviceTree dt, TreePick pick, const float* __restrict__ logp,
+__global__ void __launch_bounds__(256, PB_WIDE_WAVES_EU) wide_spec_kernel(DeviceTree dt, TreePick pick, const float* __restrict__ logp,
                                                          int64_t frame_stride, int64_t row_stride,
                                                          const int32_t* __restrict__ states0,
                                                          const int32_t* __restrict__ last0, float alpha, int T, int B,
