@@ -723,8 +723,8 @@ __global__ void __launch_bounds__(512) frames_fix_kernel(DeviceTree dt, TreePick
 template <bool FULL, int SEL, bool LEAN>
 __global__ void __launch_bounds__(LEAN ? 64 : 256) step_wave_kernel(
     const float* __restrict__ logp, int64_t row_stride, const int32_t* __restrict__ states_in,
-    const float* __restrict__ root_score, const int32_t* __restrict__ last_in, float alpha, int B,
-    int32_t* __restrict__ tokens, int32_t* __restrict__ states_out, float* __restrict__ scores, DeviceTree dt,
+    const float* __restrict__ root_score, const int32_t* __restrict__ last_in, float alpha, int blank,
+    int32_t* __restrict__ tokens, int B, int32_t* __restrict__ states_out, float* __restrict__ scores, DeviceTree dt,
     TreePick pick) {
   extern __shared__ float lds[];
   const int lane = threadIdx.x & 63, wave = LEAN ? 0 : uniform_i(threadIdx.x >> 6);
@@ -747,6 +747,21 @@ __global__ void __launch_bounds__(LEAN ? 64 : 256) step_wave_kernel(
   int last = -1;
   if (SEL == 2 && last_in != nullptr) last = last_in[b];
   __builtin_amdgcn_sched_barrier(0);  // (all of the above is in flight before the first wait)
+  // A lone wave issues one instruction every few cycles whatever it is, so what comes after the state's record
+  // has arrived is kept short: the boost of a token is am * (p_root + root_score) with am = alpha, except in the
+  // one slot of the one lane that holds the blank (0: no boost; NaN under the two-stage rules: excluded).  The
+  // multipliers depend on nothing that is loaded (`blank` is the tree's, as a leading argument like
+  // `root_score`) and are formed while the state id is on its way.
+  // (Only where the call is latency-bound: with many waves per CU the registers are worth more.)
+  float am[LEAN ? 16 : 1];
+  if constexpr (LEAN) {
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      am[j] = slot_is(j, lane, blank) ? (SEL == 0 ? 0.0f : NAN) : alpha;
+      asm volatile("" : "+v"(am[j]));  // (formed here, not where it is used)
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
   s = uniform_i(s);
   last = uniform_i(last);
   // An invalid state is decoded as the root and marked at the end: an early exit here would let the compiler
@@ -763,7 +778,12 @@ __global__ void __launch_bounds__(LEAN ? 64 : 256) step_wave_kernel(
   Cursor cur = cursor_at(t, ok ? s : 0);
   __builtin_amdgcn_sched_barrier(0);  // (the three parts of the cursor are requested together)
   float c_p = cur.p_root;
-  make_base_boost<SEL>(0, lane, t.blank, c_p, alpha, c, c);  // element-wise, in place
+  if constexpr (LEAN) {
+#pragma unroll
+    for (int j = 0; j < 16; ++j) c[j] = __fmul_rn(am[j], __fadd_rn(c_p, c[j]));  // base boosts, in place
+  } else {
+    make_base_boost<SEL>(0, lane, t.blank, c_p, alpha, c, c);  // element-wise, in place
+  }
   float val;
   int tok;
   bool row_in_lds = false;
@@ -952,7 +972,8 @@ int launch_step_wave(const DeviceTree& t, const TreePick& pick, const float* d_l
   const bool full = t.vocab_size == kChunk;
 #define PB_STEP(FULL, SEL, LEAN)                                                                                   \
   hipLaunchKernelGGL((step_wave_kernel<FULL, SEL, LEAN>), grid, block, lds, stream, d_logp, row_stride,            \
-                     d_states_in, t.root_score, d_last, alpha, B, d_tokens, d_states_out, d_scores, t, pick)
+                     d_states_in, t.root_score, d_last, alpha, t.blank_id, d_tokens, B, d_states_out, d_scores, t,  \
+                     pick)
 #define PB_LAUNCH(FULL, SEL)   \
   if (lean) {                  \
     PB_STEP(FULL, SEL, true);  \
