@@ -16,7 +16,10 @@ __device__ __forceinline__ bool pick_tree(const TreePick& p, int i, DeviceTree& 
 }
 
 constexpr int kMaxChunk = 8192;   // tokens per LDS pass of the fused kernels (64 KiB of 8-byte entries)
-constexpr int kScoreTile = 2048;  // tokens per workgroup of the score kernel (16 KiB of LDS)
+#ifndef PB_SCORE_TILE
+#define PB_SCORE_TILE 2048
+#endif
+constexpr int kScoreTile = PB_SCORE_TILE;  // tokens per workgroup of the score kernel (16 KiB of LDS)
 
 int launch_score(const DeviceTree& t, const TreePick& pick, const int32_t* d_states, int32_t B, float* d_scores,
                  int32_t* d_next, hipStream_t stream);
