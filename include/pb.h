@@ -118,8 +118,9 @@ typedef struct {
  *   Host-synchronous.  On success *out receives the tree (free with pb_free); on failure *out is
  *   untouched.  PB_EINVAL: null argument, V <= 0, blank_id outside [-1, V), unknown weight_mode,
  *   offsets not strictly increasing (an empty phrase), a phrase containing blank_id or eos_id,
- *   eos_id outside [-1, V) or equal to blank_id.
- *   PB_ERANGE: a token outside [0, V).  PB_EHIP / PB_ENOMEM: upload failed.
+ *   eos_id outside [-1, V) or equal to blank_id, a weight, beta, unk_score or final_eos_score that is not
+ *   finite.  PB_ERANGE: a token outside [0, V), or scores that add up to an overflow.
+ *   PB_EHIP / PB_ENOMEM: upload failed.
  */
 int pb_build(const int32_t* tokens, const int64_t* offsets, int64_t n_phrases, const float* weights,
              const pb_build_opts* opts, pb_tree** out);

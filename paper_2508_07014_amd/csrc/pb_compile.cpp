@@ -46,6 +46,11 @@ int compile_tree(const int32_t* tokens, const int64_t* offsets, int64_t n_phrase
     return PB_EINVAL;
   if (o.eos_id < -1 || o.eos_id >= V || (o.eos_id >= 0 && o.eos_id == o.blank_id)) return PB_EINVAL;
   if (n_phrases > 0 && (!tokens || !offsets)) return PB_EINVAL;
+  // Scores are sums of the weights: the kernels' arithmetic (a boost times 0 for the blank column, comparisons
+  // of fused values) assumes they are finite.
+  if (!std::isfinite(o.beta) || !std::isfinite(o.unk_score) || !std::isfinite(o.final_eos_score)) return PB_EINVAL;
+  for (int64_t i = 0; weights && i < n_phrases; ++i)
+    if (!std::isfinite(weights[i])) return PB_EINVAL;
   for (int64_t i = 0; i < n_phrases; ++i) {
     if (offsets[i] < 0 || offsets[i + 1] <= offsets[i]) return PB_EINVAL;
     for (int64_t j = offsets[i]; j < offsets[i + 1]; ++j) {
@@ -244,6 +249,13 @@ int compile_tree(const int32_t* tokens, const int64_t* offsets, int64_t n_phrase
     }
     t.arc.resize(t.arc_token.size());
     for (size_t j = 0; j < t.arc.size(); ++j) t.arc[j] = {t.arc_token[j], t.arc_score[j]};
+    // (finite weights can still add up to an overflow)
+    for (const float v : t.arc_score)
+      if (!std::isfinite(v)) return PB_ERANGE;
+    for (const float v : t.p_root)
+      if (!std::isfinite(v)) return PB_ERANGE;
+    for (const float v : t.backoff)
+      if (!std::isfinite(v)) return PB_ERANGE;
     out = std::move(t);
   } catch (const std::bad_alloc&) {
     return PB_ENOMEM;

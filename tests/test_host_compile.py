@@ -151,6 +151,36 @@ def test_build_error_codes(bad, code):
     assert e.value.code == code
 
 
+@pytest.mark.parametrize("what", ["weight_inf", "weight_nan", "unk_inf", "beta_nan", "final_eos_inf", "overflow"])
+def test_build_rejects_weights_that_are_not_finite(what):
+    """The kernels multiply a boost by 0 for the blank column and compare fused values: scores must be finite."""
+    toks = np.array([1, 2, 3, 4], np.int32)
+    offs = np.array([0, 2, 4], np.int64)
+    kw = dict(weights=np.array([1.0, 2.0], np.float32), weight_mode=pb.PB_W_UNIFORM, device=-1)
+    code = pb.PB_EINVAL
+    if what == "weight_inf":
+        kw["weights"] = np.array([1.0, np.inf], np.float32)
+    elif what == "weight_nan":
+        kw["weights"] = np.array([np.nan, 1.0], np.float32)
+    elif what == "unk_inf":
+        kw["unk_score"] = -np.inf
+    elif what == "beta_nan":
+        kw["beta"] = np.nan
+    elif what == "final_eos_inf":
+        kw.update(eos_id=7, final_eos_score=np.inf)
+    elif what == "overflow":  # finite weights whose sum along a phrase is not
+        toks = np.array([1, 2, 3, 4, 5, 6], np.int32)
+        offs = np.array([0, 6], np.int64)
+        kw["weights"] = np.array([3.0e38], np.float32)
+        code = pb.PB_ERANGE
+    with pytest.raises(pb.PbError) as e:
+        pb.pb_build(toks, offs, 8, 0, **kw)
+    assert e.value.code == code
+    ok = pb.pb_build(np.array([1, 2, 3, 4], np.int32), np.array([0, 2, 4], np.int64), 8, 0,
+                     weights=np.array([1.0, 2.0], np.float32), device=-1)  # the same list with finite weights builds
+    assert pb.pb_info(ok)["num_states"] == 5
+
+
 def test_step_calls_on_host_only_tree_are_rejected_not_crashing():
     tr = pb.pb_build(np.array([1, 2], np.int32), np.array([0, 2], np.int64), 8, 0, device=-1)
     for call in (lambda: pb.pb_score(tr, 0, 1, 0),
