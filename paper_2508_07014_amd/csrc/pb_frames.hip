@@ -830,6 +830,15 @@ __global__ void __launch_bounds__(64 * kBeamWaveMaxK) beam_wave_kernel(
   const int sk = states_in[u * K + min(lane, K - 1)];  // every wave sees all K states
   const float hs_in = hyp[h];
   __builtin_amdgcn_sched_barrier(0);  // (all of the above is in flight before the first wait)
+  // per-slot multiplier of the boost (alpha; 0 in the blank's slot), formed while the states are on their way:
+  // what follows the arrival of the state's record is then two instructions per slot (see step_wave_kernel)
+  float am[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    am[j] = slot_is(j, lane, t.blank) ? 0.0f : alpha;
+    asm volatile("" : "+v"(am[j]));  // (formed here, not where it is used)
+  }
+  __builtin_amdgcn_sched_barrier(0);
   float* cand_val = lds;  // [K*K], then the flat indices and the children
   int* cand_idx = reinterpret_cast<int*>(lds + kBeamWaveMaxK * kBeamWaveMaxK);
   int* cand_nxt = cand_idx + kBeamWaveMaxK * kBeamWaveMaxK;
@@ -843,7 +852,8 @@ __global__ void __launch_bounds__(64 * kBeamWaveMaxK) beam_wave_kernel(
   const float hs = uniform_f(hs_in);
   const Cursor cur = cursor_at(t, s);
   __builtin_amdgcn_sched_barrier(0);  // (the parts of the cursor are requested together)
-  make_base_boost<0>(0, lane, t.blank, cur.p_root, alpha, c, c);  // element-wise, in place
+#pragma unroll
+  for (int j = 0; j < 16; ++j) c[j] = __fmul_rn(am[j], __fadd_rn(cur.p_root, c[j]));  // base boosts, in place
   tags_clear(tags, lane);
   store_row_lds(ov, lane, x);  // the raw row: an arc reads its log-prob here and puts its fused value in its place
   // ---- overlay: arcs of the failure chain, deepest state first ------------------------------------
@@ -899,9 +909,9 @@ __global__ void __launch_bounds__(64 * kBeamWaveMaxK) beam_wave_kernel(
       cand_idx[wave * rounds + r] = wave * V + v;
       cand_nxt[wave * rounds + r] = nx;
     }
-    const int ln = opaque(lane);
+    const int taken = slot_in_lane(opaque(lane), v);
 #pragma unroll
-    for (int j = 0; j < 16; ++j) tv[j] = slot_is(j, ln, v) ? NAN : tv[j];
+    for (int j = 0; j < 16; ++j) tv[j] = taken == j ? NAN : tv[j];
   }
   __syncthreads();
   if (wave != 0) return;

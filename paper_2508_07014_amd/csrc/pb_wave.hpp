@@ -100,6 +100,14 @@ __device__ __forceinline__ bool slot_is(int j, int lane, int rel) {
   return (slot == j) && (lane == ((rel >> 2) & 63)) && (static_cast<unsigned>(rel) < static_cast<unsigned>(kChunk));
 }
 
+// The slot in which this lane holds chunk-relative token `rel` (wave-uniform), -1 in every other lane: a test of
+// all 16 slots against it is one vector compare per slot, where slot_is takes three scalar instructions and a
+// vector one -- for a lone wave, which issues one instruction every few cycles whatever it is, the cheaper form.
+__device__ __forceinline__ int slot_in_lane(int lane, int rel) {
+  const bool here = static_cast<unsigned>(rel) < static_cast<unsigned>(kChunk) && lane == ((rel >> 2) & 63);
+  return here ? (((rel >> 8) << 2) | (rel & 3)) : -1;
+}
+
 __device__ __forceinline__ bool valid_state(const TreeView& t, int s) {
   return static_cast<unsigned>(s) < static_cast<unsigned>(t.num_states);
 }
