@@ -443,6 +443,22 @@ __device__ __forceinline__ void fix_segments(int T, int B, int b, int seg_len, i
                                              int32_t* states, float* scores, const int32_t* __restrict__ patches,
                                              int* assumed, int* assumed_tok, unsigned* bad_words, int lane, int wave,
                                              int nwaves, Rerun&& rerun) {
+  auto end_word_ptr = [&](int seg) { return states + static_cast<size_t>(seg_begin(seg + 1, T, nseg) - 1) * B + b; };
+  auto end_word_of = [&](int seg) {  // state word of the last frame of segment `seg` (boundary bit included)
+    return peek_i32(end_word_ptr(seg));
+  };
+  auto end_token_of = [&](int seg) {  // label of the last frame of segment `seg`
+    if (!WITH_TOKENS) return -1;
+    return peek_i32(tokens + static_cast<size_t>(seg_begin(seg + 1, T, nseg) - 1) * B + b);
+  };
+  // (Requested before the patches are copied, so that the two accesses overlap: a patch covers frames at the start
+  // of a segment and never its last one, whose state word and label these are.)
+  const bool has = lane >= 1 && lane < nseg;
+  int words = -1, labels = -1;
+  if (wave == 0) {
+    words = has ? end_word_of(lane - 1) : -1;
+    labels = has ? end_token_of(lane - 1) : -1;
+  }
   if (patches != nullptr) {
     // a quarter wave per boundary: lane q of the quarter copies entry q of the patch
     const int sub = lane >> 4, q = lane & 15;
@@ -462,22 +478,10 @@ __device__ __forceinline__ void fix_segments(int T, int B, int b, int seg_len, i
       }
     }
   }
-  auto end_word_ptr = [&](int seg) { return states + static_cast<size_t>(seg_begin(seg + 1, T, nseg) - 1) * B + b; };
-  auto end_word_of = [&](int seg) {  // state word of the last frame of segment `seg` (boundary bit included)
-    return peek_i32(end_word_ptr(seg));
-  };
-  auto end_token_of = [&](int seg) {  // label of the last frame of segment `seg`
-    if (!WITH_TOKENS) return -1;
-    return peek_i32(tokens + static_cast<size_t>(seg_begin(seg + 1, T, nseg) - 1) * B + b);
-  };
   // Wave 0 reads the outcome before every segment in one access (lane j: the end of segment j - 1), records
   // it as what segment j is decided from, and publishes the set of segments whose guess is not certified; the
   // k-th of them goes to wave k mod nwaves, so that the re-runs spread evenly over the waves.
-  const bool has = lane >= 1 && lane < nseg;
-  int words = -1;
   if (wave == 0) {
-    words = has ? end_word_of(lane - 1) : -1;
-    const int labels = has ? end_token_of(lane - 1) : -1;
     if (has) {
       assumed[lane] = plain_state(words);
       assumed_tok[lane] = labels;
