@@ -472,7 +472,8 @@ def side_measurements(torch, pb, W, dev, stream, cfg, toks, offs, tree, info, lo
             pb.pb_score(tr, st, Bs, sc[k[0] % n], nx[k[0] % n], stream)
             k[0] += 1
 
-        fn()
+        for _ in range(5):  # (the launches before may have been of another kernel: let the clocks settle)
+            fn()
         ms = _events(torch, fn, max(20, n))
         r = _rate(Bs * V5 * 8 + 4 * Bs, ms)
         r["scores_per_s"] = Bs * V5 / (ms * 1e-3)
