@@ -717,8 +717,8 @@ __global__ void __launch_bounds__(512) frames_fix_kernel(DeviceTree dt, TreePick
 // set by the order of its requests: the row, the root scores and the state id are requested together before
 // anything is waited for, then the state's record, accumulated backoff and EOS boost together, then the arcs.
 // LEAN: one wave per workgroup and one tree for all rows -- the grid is exactly B, no argument has to arrive
-// before the requests go out and nothing but the hypothesis index separates the waves.  Otherwise (a table of
-// trees, every hypothesis naming its own) four waves per workgroup.
+// before the requests go out and nothing but the hypothesis index separates the waves.  Otherwise a table of
+// trees, every hypothesis naming its own (launched with one wave per workgroup as well; any number works).
 template <bool FULL, int SEL, bool LEAN>
 __global__ void __launch_bounds__(LEAN ? 64 : 256) step_wave_kernel(
     const float* __restrict__ logp, int64_t row_stride, const int32_t* __restrict__ states_in,
@@ -979,11 +979,11 @@ int launch_step_wave(const DeviceTree& t, const TreePick& pick, const float* d_l
   if (t.vocab_size > kChunk)
     return launch_step_wide(t, pick, d_logp, row_stride, d_states_in, d_last, alpha, B, sel, d_tokens, d_states_out,
                             d_scores, stream);
-  // One tree for all rows: one wave per workgroup at every batch size (measured against four waves per workgroup
-  // from B = 128 to B = 65536: never slower, 12 % faster at B = 65536 on states of all depths -- no wave waits for
-  // the slowest of its workgroup, and a small batch spreads over as many CUs as it has rows).
+  // One wave per workgroup at every batch size (measured against four waves per workgroup from B = 128 to
+  // B = 65536: never slower, 12 % faster at B = 65536 on states of all depths -- no wave waits for the slowest of
+  // its workgroup, and a small batch spreads over as many CUs as it has rows).  `lean`: one tree for all rows.
   const bool lean = pick.table == nullptr;
-  const int waves = lean ? 1 : 4;
+  const int waves = 1;  // (also with a table of trees: 68.7 against 73.7 us at B = 65536, 5.8 against 6.4 us at B = 128)
   const dim3 grid(static_cast<unsigned>((B + waves - 1) / waves)), block(static_cast<unsigned>(64 * waves));
   const size_t lds = static_cast<size_t>(waves) * kWaveLdsBytes;
   const bool full = t.vocab_size == kChunk;
